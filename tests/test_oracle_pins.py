@@ -1,0 +1,258 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (all CPU, no GPU).
+
+Each test names the mistake it is meant to catch.  Brute-force references are in ``brute.py``
+(float64, full N x N, no tiling, no online recurrence).
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import brute
+from oracle.lite_attn_oracle import oracle_step
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+NINF = -float("inf")
+
+
+def rand_bf16(rng, shape, scale=1.0):
+    x = torch.from_numpy(rng.standard_normal(shape).astype(np.float32) * scale).to(torch.bfloat16)
+    return x.view(torch.int16).numpy().view(np.uint16)
+
+
+def rand_qkv_with_weak_tiles(rng, B, H, N, d, tk, weak_frac=0.5, strong=2.5):
+    """Random Q, K, V whose K columns are scaled per K/V tile: "weak" tiles (scale 0.02) score far below
+    the running max set by "strong" tiles, so they fire the predicate; tile 0 is always strong."""
+    Tk = -(-N // tk)
+    scale = np.where(rng.random(Tk) < weak_frac, 0.02, strong)
+    scale[0] = strong
+    scale[1] = 0.02
+    if Tk > 2:
+        scale[2] = strong
+    col = np.repeat(scale, tk)[:N].astype(np.float32)
+    q = rng.standard_normal((B, H, N, d)).astype(np.float32) * strong
+    k = rng.standard_normal((B, H, N, d)).astype(np.float32) * col[None, None, :, None]
+    v = rng.standard_normal((B, H, N, d)).astype(np.float32)
+    def bits(x):
+        return torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    return bits(q), bits(k), bits(v)
+
+
+def empty_mask(B, H, N, tq, tk):
+    return np.zeros((B, H, -(-N // tq), -(-N // tk)), dtype=np.uint8)
+
+
+# ---------------------------------------------------------------- dense definition (eqs. 1-3)
+@pytest.mark.parametrize("N,d,tq,tk", [(256, 32, 64, 64), (200, 64, 64, 32), (300, 128, 128, 128), (97, 16, 32, 48)])
+@pytest.mark.parametrize("f64", [False, True])
+def test_threshold_disabled_equals_dense_softmax_attention(N, d, tq, tk, f64):
+    """Catches: dropped rescale of l or O, wrong V row, missing 1/sqrt(d), tail columns/rows mishandled."""
+    rng = np.random.default_rng(1)
+    B, H = 2, 3
+    q, k, v = (rand_bf16(rng, (B, H, N, d), 1.5) for _ in range(3))
+    out, mexit, g = oracle_step(q, k, v, empty_mask(B, H, N, tq, tk), NINF, tile_q=tq, tile_k=tk, f64=f64)
+    assert not mexit.any()
+    for b in range(B):
+        for h in range(H):
+            ref = brute.dense_attention(brute.widen(q[b, h]), brute.widen(k[b, h]), brute.widen(v[b, h]))
+            tol = 1e-12 if f64 else 2e-5
+            assert np.abs(out[b, h] - ref).max() <= tol * max(1.0, np.abs(ref).max())
+    assert not np.isnan(g).any() and (g <= 0).all()
+
+
+def test_strided_bnhd_layout_matches_bhnd():
+    """Catches: a stride used for the wrong axis."""
+    rng = np.random.default_rng(2)
+    B, H, N, d = 2, 3, 130, 32
+    base = [rand_bf16(rng, (B, N, H, d)) for _ in range(3)]
+    strided = [np.transpose(x, (0, 2, 1, 3)) for x in base]              # views [B,H,N,d] over [B,N,H,d]
+    packed = [np.ascontiguousarray(x) for x in strided]
+    m = empty_mask(B, H, N, 64, 64)
+    o1, m1, g1 = oracle_step(*strided, m, -1.0, tile_q=64, tile_k=64)
+    o2, m2, g2 = oracle_step(*packed, m, -1.0, tile_q=64, tile_k=64)
+    assert np.array_equal(o1, o2) and np.array_equal(m1, m2) and np.array_equal(g1, g2, equal_nan=True)
+
+
+# ---------------------------------------------------------------- output given a live set (Alg. 2)
+@pytest.mark.parametrize("immediate", [False, True])
+def test_output_is_softmax_over_live_tiles(immediate):
+    """Deferred: a tile that fires still contributes in this step (live = not masked on entry).
+    Immediate (Algorithm 2 literally): it does not (live = not masked on exit).
+    Catches: skipped tile leaking into the denominator or the running max; wrong mode semantics."""
+    rng = np.random.default_rng(3)
+    B, H, N, d, tq, tk = 1, 2, 320, 32, 64, 32
+    q, k, v = rand_qkv_with_weak_tiles(rng, B, H, N, d, tk)
+    Tq, Tk = -(-N // tq), -(-N // tk)
+    entry = (rng.random((B, H, Tq, Tk)) < 0.4).astype(np.uint8)
+    entry[..., 0] = 0                                                  # keep one (strong) live tile per row
+    thr = -1.5
+    out, mexit, g = oracle_step(q, k, v, entry, thr, tile_q=tq, tile_k=tk, immediate=immediate, f64=True)
+    assert (mexit >= entry).all() and (mexit != entry).any(), "test needs some tiles to fire"
+    for h in range(H):
+        live = (mexit[0, h] == 0) if immediate else (entry[0, h] == 0)
+        ref = brute.dense_attention(brute.widen(q[0, h]), brute.widen(k[0, h]), brute.widen(v[0, h]),
+                                    brute.expand_tiles(live, tq, tk, N))
+        assert np.abs(out[0, h] - ref).max() <= 1e-11
+
+
+# ---------------------------------------------------------------- predicate values (eq. sparge_cond)
+@pytest.mark.parametrize("N,d,tq,tk", [(256, 32, 64, 64), (210, 64, 32, 64), (384, 128, 128, 128)])
+def test_predicate_values_match_prefix_max_formula(N, d, tq, tk):
+    """Catches: sign of the difference, min/max over rows swapped, running max including skipped tiles
+    or the current tile left out of m_ij, '<' vs '<='."""
+    rng = np.random.default_rng(4)
+    q, k, v = rand_qkv_with_weak_tiles(rng, 1, 1, N, d, tk)
+    Tq, Tk = -(-N // tq), -(-N // tk)
+    entry = (rng.random((1, 1, Tq, Tk)) < 0.3).astype(np.uint8)
+    entry[..., 0] = 0
+    thr = -1.0
+    out, mexit, g = oracle_step(q, k, v, entry, thr, tile_q=tq, tile_k=tk, f64=True)
+    gb = brute.predicate_values(brute.widen(q[0, 0]), brute.widen(k[0, 0]), entry[0, 0], tq, tk)
+    assert np.array_equal(np.isnan(g[0, 0]), np.isnan(gb))
+    assert np.nanmax(np.abs(g[0, 0] - gb)) <= 1e-12
+    fired = np.where(np.isnan(gb), False, gb <= thr)
+    assert np.array_equal(mexit[0, 0] != 0, (entry[0, 0] != 0) | fired)
+    assert fired.any() and (~fired & (entry[0, 0] == 0)).any()
+    # the same in fp32: predicate values agree to rounding
+    _, _, g32 = oracle_step(q, k, v, entry, thr, tile_q=tq, tile_k=tk, f64=False)
+    assert np.nanmax(np.abs(g32[0, 0] - gb)) <= 1e-5
+
+
+def test_fired_tiles_have_exponentially_small_weights():
+    """The paper's consequence of the predicate: max(P~_ij) <= e^{-eps} on every fired tile."""
+    rng = np.random.default_rng(5)
+    N, d, t = 256, 32, 32
+    q, k, v = rand_qkv_with_weak_tiles(rng, 1, 1, N, d, t)
+    thr = -2.0
+    _, mexit, _ = oracle_step(q, k, v, empty_mask(1, 1, N, t, t), thr, tile_q=t, tile_k=t, f64=True)
+    s = brute.scores(brute.widen(q[0, 0]), brute.widen(k[0, 0]))
+    T = N // t
+    assert mexit.any()
+    for i in range(T):
+        for j in range(T):
+            if mexit[0, 0, i, j]:
+                blk = s[i * t:(i + 1) * t, j * t:(j + 1) * t]
+                run = s[i * t:(i + 1) * t, :(j + 1) * t].max(axis=1, keepdims=True)   # nothing masked on entry
+                assert np.exp(blk - run).max() <= np.exp(thr) * (1 + 1e-12)
+
+
+# ---------------------------------------------------------------- closed-form two-tile case
+def test_two_tile_closed_form():
+    """Fixture derived by hand from eq. (sparge_cond) and eqs. 1-3 (see the JSON's `derivation`)."""
+    with open(os.path.join(GOLDEN, "two_tile_closed_form.json")) as f:
+        gold = json.load(f)
+    d, t, N = gold["head_dim"], gold["tile"], gold["seqlen"]
+    def bf(x):
+        return torch.tensor(x, dtype=torch.float32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    q = np.zeros((1, 1, N, d), np.float32); q[..., 0] = gold["q0"]
+    k = np.zeros((1, 1, N, d), np.float32); k[0, 0, :t, 0] = gold["k0_tile0"]; k[0, 0, t:, 0] = gold["k0_tile1"]
+    v = np.zeros((1, 1, N, d), np.float32); v[0, 0, :t, :] = gold["v_tile0"]; v[0, 0, t:, :] = gold["v_tile1"]
+    q, k, v = bf(q), bf(k), bf(v)
+    for case in gold["cases"]:
+        m0 = empty_mask(1, 1, N, t, t)
+        out, m1, g = oracle_step(q, k, v, m0, case["threshold"], tile_q=t, tile_k=t)
+        assert np.allclose(g[0, 0], np.array(gold["g"]), atol=1e-6)
+        assert m1[0, 0].tolist() == case["mask_after_step0"]
+        assert np.allclose(out, case["out_step0"], rtol=2e-6)
+        out2, m2, g2 = oracle_step(q, k, v, m1, case["threshold"], tile_q=t, tile_k=t)
+        assert m2[0, 0].tolist() == case["mask_after_step0"]
+        assert np.allclose(out2, case["out_step1"], rtol=2e-6)
+        # immediate mode drops the fired tile in the same step
+        out_i, m_i, _ = oracle_step(q, k, v, m0, case["threshold"], tile_q=t, tile_k=t, immediate=True)
+        assert np.array_equal(m_i, m1) and np.allclose(out_i, case["out_step1"], rtol=2e-6)
+
+
+# ---------------------------------------------------------------- mask evolution invariants
+def _drift_steps(seed, H, N, d, steps):
+    from paper_2511_11062_amd.inputs import Workload, DriftSequence, bf16_bits
+    wl = Workload("t", 1, H, (2, 8, N // 16), steps=steps, head_dim=d, seed=seed)
+    assert wl.seqlen == N
+    seq = DriftSequence(wl, "cpu")
+    return [tuple(bf16_bits(x) for x in next(seq)) for _ in range(steps)]
+
+
+def test_mask_evolution_invariants():
+    """Monotone mask; first live tile of a row never fires; deferred and immediate modes give the same
+    masks; a disabled threshold keeps the mask empty.  Catches: mask overwritten instead of OR-ed,
+    m_{i,-1} not -inf, the immediate `continue` changing the running max."""
+    H, N, d, t, steps = 2, 512, 32, 64, 4
+    thrs = [-2.0, -1.5, -1.0, -0.7]          # raised over the steps, as in the paper's ablation setting
+    data = _drift_steps(7, H, N, d, steps)
+    T = N // t
+    md = empty_mask(1, H, N, t, t); mi = md.copy(); mz = md.copy()
+    counts = []
+    for (q, k, v), thr in zip(data, thrs):
+        first_live = np.argmax(md[0] == 0, axis=2)                      # [H,Tq]
+        _, md_new, g = oracle_step(q, k, v, md, thr, tile_q=t, tile_k=t)
+        _, mi_new, _ = oracle_step(q, k, v, mi, thr, tile_q=t, tile_k=t, immediate=True)
+        _, mz, _ = oracle_step(q, k, v, mz, NINF, tile_q=t, tile_k=t)
+        assert ((md_new != 0) | (md == 0)).all(), "a skipped tile was un-skipped"
+        assert np.array_equal(md_new, mi_new)
+        assert (np.isnan(g) == (md != 0)).all()
+        for h in range(H):
+            for i in range(T):
+                assert md_new[0, h, i, first_live[h, i]] == 0
+                assert g[0, h, i, first_live[h, i]] == 0.0
+        assert (md_new == 0).any(axis=3).all(), "every row keeps a live tile"
+        md, mi = md_new, mi_new
+        counts.append(int(md.sum()))
+    assert not mz.any()
+    assert counts == sorted(counts) and counts[0] > 0 and counts[-1] > counts[0]
+
+
+def test_first_tile_never_fires_when_all_scores_are_negative():
+    """m_{i,-1} is -inf, not 0: with every score negative the first live tile still has g = 0."""
+    rng = np.random.default_rng(11)
+    N, d, t = 256, 32, 64
+    q = np.abs(rng.standard_normal((1, 1, N, d))).astype(np.float32)
+    k = -np.abs(rng.standard_normal((1, 1, N, d))).astype(np.float32)
+    def bits(x):
+        return torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    q, k, v = bits(q), bits(k), rand_bf16(rng, (1, 1, N, d))
+    entry = empty_mask(1, 1, N, t, t); entry[0, 0, 1, 0] = 1; entry[0, 0, 2, :2] = 1
+    _, mexit, g = oracle_step(q, k, v, entry, -0.01, tile_q=t, tile_k=t, f64=True)
+    gb = brute.predicate_values(brute.widen(q[0, 0]), brute.widen(k[0, 0]), entry[0, 0], t, t)
+    assert np.nanmax(np.abs(g[0, 0] - gb)) <= 1e-12
+    for i, first in enumerate([0, 1, 2, 0]):
+        assert g[0, 0, i, first] == 0.0 and mexit[0, 0, i, first] == 0
+
+
+def test_pinned_tiles_never_fire():
+    """Tiles whose Q rows or K/V columns intersect the protected token range are evaluated but never
+    marked (benchmark requirement for text tokens; not from the paper)."""
+    rng = np.random.default_rng(8)
+    N, d, t = 400, 32, 64                    # protected range 300..349 straddles tiles 4 and 5; tail tile 6
+    q, k, v = rand_qkv_with_weak_tiles(rng, 1, 1, N, d, t, weak_frac=0.9)
+    thr = -0.5
+    m0 = empty_mask(1, 1, N, t, t)
+    _, free, g0 = oracle_step(q, k, v, m0, thr, tile_q=t, tile_k=t)
+    _, pinned, g1 = oracle_step(q, k, v, m0, thr, tile_q=t, tile_k=t, protect=(300, 50))
+    assert np.array_equal(g0, g1)
+    assert free[0, 0, 4:6, :].any() and free[0, 0, :, 4:6].any(), "test needs unprotected firing there"
+    expect = free.copy(); expect[0, 0, 4:6, :] = 0; expect[0, 0, :, 4:6] = 0
+    assert np.array_equal(pinned, expect)
+
+
+def test_row_subset_equals_full_run():
+    rng = np.random.default_rng(9)
+    B, H, N, d, t = 1, 2, 256, 32, 64
+    q, k, v = (rand_bf16(rng, (B, H, N, d), 2.0) for _ in range(3))
+    m0 = empty_mask(B, H, N, t, t)
+    of, mf, gf = oracle_step(q, k, v, m0, -1.0, tile_q=t, tile_k=t)
+    rows = [1, 6]
+    os_, ms, gs = oracle_step(q, k, v, m0, -1.0, tile_q=t, tile_k=t, rows=rows)
+    for r in rows:
+        h, i = divmod(r, N // t)
+        assert np.array_equal(os_[0, h, i * t:(i + 1) * t], of[0, h, i * t:(i + 1) * t])
+        assert np.array_equal(ms[0, h, i], mf[0, h, i]) and np.array_equal(gs[0, h, i], gf[0, h, i])
+    assert np.isnan(os_[0, 0, 0]).all() and not ms[0, 0, 0].any()
+
+
+def test_rejects_nonnegative_threshold():
+    rng = np.random.default_rng(10)
+    q, k, v = (rand_bf16(rng, (1, 1, 64, 16)) for _ in range(3))
+    for bad in (0.0, 1.0, float("nan")):
+        with pytest.raises(ValueError):
+            oracle_step(q, k, v, empty_mask(1, 1, 64, 32, 32), bad, tile_q=32, tile_k=32)
