@@ -1,0 +1,117 @@
+/*
+ * lite_attn.h -- C ABI of the MI355X (gfx950) LiteAttention forward path.
+ *
+ * One call of lite_attn_fwd is one self-attention call of one transformer
+ * layer at one denoising timestep: a tiled FlashAttention-style forward
+ * (S = Q K^T / sqrt(d), online softmax, O = P V; paper Preliminaries,
+ * eqs. 1-3 and the tile recurrences after them) that
+ *   - visits, for every Q tile, only the K/V tiles whose Skip-Mask bit is
+ *     clear (Method, Algorithm 2 "QK-Skip"; Implementation, "Producer and
+ *     Skip-List Optimization"),
+ *   - evaluates the local skip predicate max(m_local - m_ij) <= -eps on every
+ *     visited tile during the online softmax (Preliminaries, eq. sparge_cond;
+ *     Implementation, "Skip-Mask Evaluation Mechanism"),
+ *   - and sets the Skip-Mask bit of every tile the predicate marks; bits are
+ *     only ever set, and a bit set in this call takes effect from the next
+ *     call on (the marked tile is still accumulated in the call that marks
+ *     it, as the Implementation section describes).
+ * The Skip-Mask persists in the handle across calls (timesteps).
+ *
+ * All pointers named q, k, v, out are DEVICE pointers to bf16; everything
+ * named host_* is a HOST pointer.  No function throws or aborts; every
+ * function returning int returns 0 on success or a negative lite_attn_error.
+ * The library never synchronises the device inside lite_attn_fwd.
+ */
+#ifndef LITE_ATTN_H
+#define LITE_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LITE_ATTN_OK = 0,
+  LITE_ATTN_EINVAL = -1,       /* null pointer, non-positive size, threshold >= 0 or NaN, bad stride */
+  LITE_ATTN_ESTEP = -2,        /* step is neither 0 nor last step + 1, or >= max_steps */
+  LITE_ATTN_EUNSUPPORTED = -3, /* head_dim != 128, tile_q/tile_k != 128, more than 65535 K/V tiles */
+  LITE_ATTN_ENOMEM = -4,       /* host or device allocation failed */
+  LITE_ATTN_EHIP = -5          /* a HIP runtime call failed; lite_attn_last_hip_error() has its code */
+} lite_attn_error;
+
+/* Shape of one attention layer; fixed for the life of a handle. */
+typedef struct {
+  int32_t batch, heads, seqlen, head_dim; /* head_dim must be 128 */
+  int32_t tile_q, tile_k;                 /* Skip-Mask granularity (rows x columns of S per bit); must be 128, 128 */
+  int64_t stride_b, stride_h, stride_n;   /* element strides shared by q, k, v and out; head_dim is contiguous.
+                                             [B,H,N,d]: (H*N*d, N*d, d);  [B,N,H,d]: (N*H*d, d, H*d) */
+  int32_t protect_start, protect_len;     /* token range [start, start+len) never skipped: a tile whose Q rows or
+                                             K/V columns intersect it is evaluated but never marked; len 0 = none */
+  int32_t flags;                          /* must be 0 (reserved) */
+  int32_t max_steps;                      /* capacity of the per-step statistics, >= 1 */
+} lite_attn_desc_t;
+
+/* Opaque handle: owns the device Skip-Mask ([B,H,Tq,ceil(Tk/64)] uint64, bit j%64 of word j/64 set = tile (i,j)
+   skipped), the Skip-List buffers and the statistics.  Tq = ceil(N/tile_q), Tk = ceil(N/tile_k). */
+typedef struct lite_attn_mask lite_attn_mask_t;
+
+typedef struct {
+  int32_t step;
+  uint64_t tiles_total;        /* B*H*Tq*Tk */
+  uint64_t tiles_skipped_in;   /* tiles already marked when the step started (not visited) */
+  uint64_t tiles_newly_marked; /* tiles the predicate marked during the step */
+  uint64_t live_list_bytes;    /* bytes of Skip-List entries the attention kernel consumed */
+} lite_attn_stats_t;
+
+/* Allocates the handle and its device buffers on the current HIP device and clears the mask.
+   Paper: the Skip-Mask is a persistent per-layer, per-head structure (Implementation, "LiteAttention").
+   *out is written only on success.  Uses the null stream until lite_attn_set_stream. */
+int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out);
+
+/* All later work of this handle is enqueued on `hip_stream` (a hipStream_t, e.g. PyTorch's current stream). */
+int lite_attn_set_stream(lite_attn_mask_t* mask, void* hip_stream);
+
+/* One attention call (Algorithm 2 with the deferred mask update, see top of file).
+     q, k, v   device bf16, layout given by the handle's strides; borrowed, not modified
+     out       device bf16, same layout; every valid row is written
+     skip_mask handle; its mask is read (via the Skip-List built from it at the start of the call) and updated
+     threshold signed -eps of eq. (sparge_cond) in natural-log units of S = QK^T/sqrt(d), must be < 0;
+               -INFINITY never marks anything (with an empty mask the result is dense attention)
+     step      0 clears the mask and the statistics first (new denoising trajectory); otherwise must be the
+               previous call's step + 1
+   Asynchronous on the handle's stream; allocates nothing. */
+int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_attn_mask_t* skip_mask,
+                  float threshold, int step);
+
+/* Statistics of one completed step (paper's sparsity = skipped fraction of tiles, Experiments "Metrics").
+   Synchronises the handle's stream. */
+int lite_attn_skip_stats(lite_attn_mask_t* mask, int step, lite_attn_stats_t* host_out);
+
+/* Number of uint64 words of the whole mask: B*H*Tq*ceil(Tk/64). */
+size_t lite_attn_mask_words(const lite_attn_mask_t* mask);
+
+/* Copy the Skip-Mask to / from host memory (`words` must equal lite_attn_mask_words).  Both synchronise the
+   stream.  Import overwrites the mask (it is the only way bits can be cleared besides step 0) and sets
+   the expected next step to `next_step` (>= 0). */
+int lite_attn_mask_export(lite_attn_mask_t* mask, uint64_t* host_bits, size_t words);
+int lite_attn_mask_import(lite_attn_mask_t* mask, const uint64_t* host_bits, size_t words, int next_step);
+
+/* Runs the Skip-List compaction on the current mask and copies the result to the host:
+     host_live_idx [B*H*Tq][Tk] uint16: for each Q-tile row the ascending indices of its live K/V tiles in the
+                                        first host_live_cnt[row] slots (the rest is unspecified)
+     host_live_cnt [B*H*Tq]     uint32
+   Paper: the Skip-List is the compressed form of the mask that the loader walks (Implementation, "Producer and
+   Skip-List Optimization"); here it is a packed index list rather than (start,end) runs.  Synchronises. */
+int lite_attn_skiplist_export(lite_attn_mask_t* mask, uint16_t* host_live_idx, uint32_t* host_live_cnt);
+
+void lite_attn_free_mask(lite_attn_mask_t* mask);
+
+const char* lite_attn_strerror(int code);
+int lite_attn_last_hip_error(void); /* hipError_t of the last failed HIP call on this thread, 0 if none */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LITE_ATTN_H */

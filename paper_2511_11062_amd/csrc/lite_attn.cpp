@@ -1,0 +1,198 @@
+// Host side of the C ABI declared in include/lite_attn.h: handle, argument checks, launches.
+#include "lite_attn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <new>
+
+#include "lite_attn_kernels.h"
+
+struct lite_attn_mask {
+  lite_attn_desc_t desc;
+  int Tq, Tk, W;
+  int64_t rows;
+  uint64_t* d_bits;
+  uint16_t* d_live_idx;
+  uint32_t* d_live_cnt;
+  unsigned long long* d_stats;  // [max_steps][2]: skipped on entry, newly marked
+  hipStream_t stream;
+  int next_step;
+};
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+int hip_fail(hipError_t e) {
+  g_last_hip = (int)e;
+  return e == hipErrorOutOfMemory ? LITE_ATTN_ENOMEM : LITE_ATTN_EHIP;
+}
+
+#define LA_HIP(expr)                        \
+  do {                                      \
+    hipError_t e_ = (expr);                 \
+    if (e_ != hipSuccess) return hip_fail(e_); \
+  } while (0)
+
+int check_desc(const lite_attn_desc_t* d) {
+  if (!d) return LITE_ATTN_EINVAL;
+  if (d->batch < 1 || d->heads < 1 || d->seqlen < 1 || d->head_dim < 1 || d->tile_q < 1 || d->tile_k < 1)
+    return LITE_ATTN_EINVAL;
+  if (d->max_steps < 1 || d->flags != 0) return LITE_ATTN_EINVAL;
+  if (d->protect_len < 0 || d->protect_start < 0 ||
+      (d->protect_len > 0 && (int64_t)d->protect_start + d->protect_len > d->seqlen))
+    return LITE_ATTN_EINVAL;
+  // 16-byte vector accesses: every stride must be a multiple of 8 bf16 elements
+  if (d->stride_n < d->head_dim || d->stride_b < 0 || d->stride_h < 0) return LITE_ATTN_EINVAL;
+  if ((d->stride_n % 8) || (d->stride_b % 8) || (d->stride_h % 8)) return LITE_ATTN_EINVAL;
+  if (d->batch > 1 && d->stride_b == 0) return LITE_ATTN_EINVAL;
+  if (d->heads > 1 && d->stride_h == 0) return LITE_ATTN_EINVAL;
+  if (d->head_dim != 128 || d->tile_q != 128 || d->tile_k != 128) return LITE_ATTN_EUNSUPPORTED;
+  const int64_t Tk = ((int64_t)d->seqlen + 127) / 128;
+  if (Tk > 65535) return LITE_ATTN_EUNSUPPORTED;
+  const int64_t rows = (int64_t)d->batch * d->heads * Tk;
+  if (rows > (int64_t)1 << 30) return LITE_ATTN_EUNSUPPORTED;
+  return LITE_ATTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out) {
+  if (!out) return LITE_ATTN_EINVAL;
+  int rc = check_desc(desc);
+  if (rc != LITE_ATTN_OK) return rc;
+  lite_attn_mask* m = new (std::nothrow) lite_attn_mask();
+  if (!m) return LITE_ATTN_ENOMEM;
+  m->desc = *desc;
+  m->Tq = (desc->seqlen + desc->tile_q - 1) / desc->tile_q;
+  m->Tk = (desc->seqlen + desc->tile_k - 1) / desc->tile_k;
+  m->W = (m->Tk + 63) / 64;
+  m->rows = (int64_t)desc->batch * desc->heads * m->Tq;
+  m->stream = nullptr;
+  m->next_step = 0;
+  m->d_bits = nullptr; m->d_live_idx = nullptr; m->d_live_cnt = nullptr; m->d_stats = nullptr;
+  hipError_t e = hipMalloc(&m->d_bits, sizeof(uint64_t) * (size_t)m->rows * m->W);
+  if (e == hipSuccess) e = hipMalloc(&m->d_live_idx, sizeof(uint16_t) * (size_t)m->rows * m->Tk);
+  if (e == hipSuccess) e = hipMalloc(&m->d_live_cnt, sizeof(uint32_t) * (size_t)m->rows);
+  if (e == hipSuccess) e = hipMalloc(&m->d_stats, sizeof(unsigned long long) * 2 * (size_t)desc->max_steps);
+  if (e == hipSuccess) e = la::prepare_fwd();
+  if (e == hipSuccess)
+    e = la::launch_clear(m->d_bits, (size_t)m->rows * m->W, m->d_stats, 2 * (size_t)desc->max_steps, m->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+  if (e != hipSuccess) {
+    lite_attn_free_mask(m);
+    return hip_fail(e);
+  }
+  *out = m;
+  return LITE_ATTN_OK;
+}
+
+int lite_attn_set_stream(lite_attn_mask_t* m, void* hip_stream) {
+  if (!m) return LITE_ATTN_EINVAL;
+  LA_HIP(hipStreamSynchronize(m->stream));  // work already queued keeps its order with what follows
+  m->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  return LITE_ATTN_OK;
+}
+
+int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_attn_mask_t* m, float threshold,
+                  int step) {
+  if (!q || !k || !v || !out || !m) return LITE_ATTN_EINVAL;
+  if (std::isnan(threshold) || threshold >= 0.f) return LITE_ATTN_EINVAL;
+  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) return LITE_ATTN_EINVAL;
+  if (step < 0 || step >= m->desc.max_steps) return LITE_ATTN_ESTEP;
+  if (step != 0 && step != m->next_step) return LITE_ATTN_ESTEP;
+  const lite_attn_desc_t& d = m->desc;
+  if (step == 0)
+    LA_HIP(la::launch_clear(m->d_bits, (size_t)m->rows * m->W, m->d_stats, 2 * (size_t)d.max_steps, m->stream));
+  unsigned long long* st = m->d_stats + 2 * (size_t)step;
+  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->d_live_idx, m->d_live_cnt, st, m->stream));
+  la::FwdParams p;
+  p.q = static_cast<const uint16_t*>(q);
+  p.k = static_cast<const uint16_t*>(k);
+  p.v = static_cast<const uint16_t*>(v);
+  p.out = static_cast<uint16_t*>(out);
+  p.stride_b = d.stride_b; p.stride_h = d.stride_h; p.stride_n = d.stride_n;
+  p.H = d.heads; p.N = d.seqlen; p.Tq = m->Tq; p.Tk = m->Tk; p.W = m->W;
+  p.live_idx = m->d_live_idx; p.live_cnt = m->d_live_cnt; p.bits = m->d_bits;
+  p.stat_newly = st + 1;
+  p.thr = threshold;
+  p.scale = 1.0f / std::sqrt((float)d.head_dim);
+  p.protect_start = d.protect_start; p.protect_len = d.protect_len;
+  p.rows_total = (int)m->rows;
+  p.rows_per_xcd = (int)((m->rows + 7) / 8);
+  LA_HIP(la::launch_fwd(p, m->stream));
+  m->next_step = step + 1;
+  return LITE_ATTN_OK;
+}
+
+int lite_attn_skip_stats(lite_attn_mask_t* m, int step, lite_attn_stats_t* host_out) {
+  if (!m || !host_out) return LITE_ATTN_EINVAL;
+  if (step < 0 || step >= m->next_step || step >= m->desc.max_steps) return LITE_ATTN_ESTEP;
+  unsigned long long raw[2];
+  LA_HIP(hipMemcpyAsync(raw, m->d_stats + 2 * (size_t)step, sizeof raw, hipMemcpyDeviceToHost, m->stream));
+  LA_HIP(hipStreamSynchronize(m->stream));
+  host_out->step = step;
+  host_out->tiles_total = (uint64_t)m->rows * (uint64_t)m->Tk;
+  host_out->tiles_skipped_in = raw[0];
+  host_out->tiles_newly_marked = raw[1];
+  host_out->live_list_bytes = (host_out->tiles_total - raw[0]) * sizeof(uint16_t);
+  return LITE_ATTN_OK;
+}
+
+size_t lite_attn_mask_words(const lite_attn_mask_t* m) { return m ? (size_t)m->rows * m->W : 0; }
+
+int lite_attn_mask_export(lite_attn_mask_t* m, uint64_t* host_bits, size_t words) {
+  if (!m || !host_bits || words != lite_attn_mask_words(m)) return LITE_ATTN_EINVAL;
+  LA_HIP(hipMemcpyAsync(host_bits, m->d_bits, words * sizeof(uint64_t), hipMemcpyDeviceToHost, m->stream));
+  LA_HIP(hipStreamSynchronize(m->stream));
+  return LITE_ATTN_OK;
+}
+
+int lite_attn_mask_import(lite_attn_mask_t* m, const uint64_t* host_bits, size_t words, int next_step) {
+  if (!m || !host_bits || words != lite_attn_mask_words(m)) return LITE_ATTN_EINVAL;
+  if (next_step < 0 || next_step >= m->desc.max_steps) return LITE_ATTN_ESTEP;
+  LA_HIP(hipMemcpyAsync(m->d_bits, host_bits, words * sizeof(uint64_t), hipMemcpyHostToDevice, m->stream));
+  LA_HIP(hipStreamSynchronize(m->stream));
+  m->next_step = next_step;
+  return LITE_ATTN_OK;
+}
+
+int lite_attn_skiplist_export(lite_attn_mask_t* m, uint16_t* host_live_idx, uint32_t* host_live_cnt) {
+  if (!m || !host_live_idx || !host_live_cnt) return LITE_ATTN_EINVAL;
+  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->d_live_idx, m->d_live_cnt, nullptr, m->stream));
+  LA_HIP(hipMemcpyAsync(host_live_idx, m->d_live_idx, sizeof(uint16_t) * (size_t)m->rows * m->Tk,
+                        hipMemcpyDeviceToHost, m->stream));
+  LA_HIP(hipMemcpyAsync(host_live_cnt, m->d_live_cnt, sizeof(uint32_t) * (size_t)m->rows, hipMemcpyDeviceToHost,
+                        m->stream));
+  LA_HIP(hipStreamSynchronize(m->stream));
+  return LITE_ATTN_OK;
+}
+
+void lite_attn_free_mask(lite_attn_mask_t* m) {
+  if (!m) return;
+  if (m->d_bits) (void)hipFree(m->d_bits);
+  if (m->d_live_idx) (void)hipFree(m->d_live_idx);
+  if (m->d_live_cnt) (void)hipFree(m->d_live_cnt);
+  if (m->d_stats) (void)hipFree(m->d_stats);
+  delete m;
+}
+
+const char* lite_attn_strerror(int code) {
+  switch (code) {
+    case LITE_ATTN_OK: return "ok";
+    case LITE_ATTN_EINVAL: return "invalid argument";
+    case LITE_ATTN_ESTEP: return "step out of sequence";
+    case LITE_ATTN_EUNSUPPORTED: return "unsupported shape (head_dim and tiles must be 128)";
+    case LITE_ATTN_ENOMEM: return "out of memory";
+    case LITE_ATTN_EHIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+int lite_attn_last_hip_error(void) { return g_last_hip; }
+
+}  // extern "C"

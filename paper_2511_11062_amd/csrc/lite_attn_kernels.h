@@ -1,0 +1,33 @@
+// Internal interface between the C-ABI host code and the gfx950 kernels (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace la {
+
+struct FwdParams {
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  uint16_t* out;
+  int64_t stride_b, stride_h, stride_n;  // elements
+  int H, N, Tq, Tk, W;                   // W = uint64 words per mask row
+  const uint16_t* live_idx;              // [rows][Tk]
+  const uint32_t* live_cnt;              // [rows]
+  uint64_t* bits;                        // [rows][W]
+  unsigned long long* stat_newly;        // counter of the current step
+  float thr;                             // signed threshold, natural-log units of S
+  float scale;                           // 1/sqrt(d)
+  int protect_start, protect_len;
+  int rows_total, rows_per_xcd;
+};
+
+int fwd_lds_bytes();
+hipError_t prepare_fwd();
+hipError_t launch_clear(uint64_t* bits, size_t words, unsigned long long* stats, size_t nstats, hipStream_t st);
+hipError_t launch_compact(const uint64_t* bits, int rows, int Tk, int W, uint16_t* live_idx, uint32_t* live_cnt,
+                          unsigned long long* stat_skipped_in, hipStream_t st);
+hipError_t launch_fwd(const FwdParams& p, hipStream_t st);
+
+}  // namespace la

@@ -1,0 +1,129 @@
+"""GPU-vs-oracle comparison of the skip-aware attention path (used by the gpu tests and the smoke check).
+
+Protocol: the oracle runs its own mask trajectory (its inputs never come from the HIP path).  Before every
+step the oracle's entry mask is imported into the HIP handle for the compared rows ("teacher forcing"), so
+that one borderline tile cannot change the inputs of later steps; then both run the step on the same
+bf16 bytes and are compared:
+  * output: max|dO| <= 1e-2 * max|O| and mean|dO| <= 1e-3;
+  * exit mask: bit-exact, except tiles whose oracle predicate value lies within 1e-3 of the threshold.
+Rows (b,h,i) are independent, so large shapes are compared on a sample of rows.
+"""
+import numpy as np
+import torch
+
+from paper_2511_11062_amd import inputs
+from oracle.lite_attn_oracle import oracle_step
+
+MAX_REL = 1e-2     # max|dO| <= MAX_REL * max|O|
+MEAN_ABS = 1e-3    # mean|dO| <= MEAN_ABS
+G_BAND = 1e-3      # |g - thr| <= G_BAND excuses a mask bit
+
+
+def pack_mask(mask_bytes: np.ndarray) -> np.ndarray:
+    """uint8 [..., Tk] (nonzero = skipped) -> uint64 [..., ceil(Tk/64)], bit j%64 of word j/64."""
+    tk = mask_bytes.shape[-1]
+    w = -(-tk // 64)
+    padded = np.zeros(mask_bytes.shape[:-1] + (w * 64,), dtype=np.uint8)
+    padded[..., :tk] = mask_bytes != 0
+    b = np.packbits(padded, axis=-1, bitorder="little")
+    return np.ascontiguousarray(b).view(np.uint64)
+
+
+def unpack_mask(bits: np.ndarray, tk: int) -> np.ndarray:
+    """inverse of pack_mask: uint64 [..., W] -> uint8 [..., tk]"""
+    by = np.ascontiguousarray(bits).view(np.uint8)
+    return np.unpackbits(by, axis=-1, bitorder="little")[..., :tk]
+
+
+def compare_output(o_gpu: np.ndarray, o_ref: np.ndarray):
+    d = np.abs(o_gpu.astype(np.float64) - o_ref.astype(np.float64))
+    return float(d.max()), float(d.mean()), float(np.abs(o_ref).max())
+
+
+def check_step(o_gpu, o_ref, m_gpu, m_ref, g_ref, thr):
+    """Raises AssertionError on a parity violation; returns a small report dict."""
+    mx, mean, omax = compare_output(o_gpu, o_ref)
+    assert np.isfinite(o_gpu).all(), "non-finite output"
+    assert mx <= MAX_REL * omax, "max|dO| = %.3e > %.1e * max|O| (%.3e)" % (mx, MAX_REL, omax)
+    assert mean <= MEAN_ABS, "mean|dO| = %.3e > %.1e" % (mean, MEAN_ABS)
+    diff = (m_gpu != 0) != (m_ref != 0)
+    with np.errstate(invalid="ignore"):
+        excused = np.abs(g_ref - thr) <= G_BAND      # NaN (tile not evaluated) is never excused
+    bad = diff & ~excused
+    assert not bad.any(), "%d mask bits differ outside the +-%.0e band (first at %s)" % (
+        int(bad.sum()), G_BAND, tuple(np.argwhere(bad)[0]))
+    return {"max_dO": mx, "mean_dO": mean, "max_O": omax, "mask_excused": int((diff & excused).sum()),
+            "skipped_out": float((m_ref != 0).mean())}
+
+
+def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sample_rows=None, gen_device=None,
+                       verbose=False, seed=0, layout="bhnd"):
+    """Runs `steps` denoising steps of a named workload on cuda:0 through the C ABI and checks every step.
+
+    sample_rows: None = all rows; an int = that many seeded random rows plus first/last (and protected) rows.
+    Returns the list of per-step reports."""
+    from paper_2511_11062_amd import lite_attn as la
+    wl = inputs.WORKLOADS[workload] if isinstance(workload, str) else workload
+    steps = steps or wl.steps
+    dev = torch.device("cuda:0")
+    B, H, N, d = wl.batch, wl.heads, wl.seqlen, wl.head_dim
+    Tq = Tk = -(-N // 128)
+    W = -(-Tk // 64)
+    if sample_rows is None:
+        rows = np.arange(B * H * Tq)
+    else:
+        rng = np.random.default_rng(seed)
+        base = {0, Tq - 1, B * H * Tq - 1, (B * H - 1) * Tq}
+        if wl.text_tokens:
+            base |= {wl.video_tokens // 128, wl.video_tokens // 128 - 1, Tq + wl.video_tokens // 128}
+        rows = np.array(sorted(base | set(rng.choice(B * H * Tq, size=sample_rows, replace=False).tolist())))
+    heads = sorted({int(r // Tq) for r in rows})            # flattened (b*H+h)
+    head_pos = {bh: n for n, bh in enumerate(heads)}
+    sub_rows = [head_pos[int(r // Tq)] * Tq + int(r % Tq) for r in rows]
+
+    seq = inputs.DriftSequence(wl, gen_device or ("cpu" if B * H * N <= 1 << 16 else dev))
+    strides = None if layout == "bhnd" else (N * H * d, d, H * d)       # "bnhd": memory order [B,N,H,d]
+    handle = la.lite_attn_init_mask(B, H, N, protect=wl.protect, max_steps=max(steps, 1), strides=strides)
+    la.lite_attn_set_stream(handle, torch.cuda.current_stream().cuda_stream)
+    m_ref = np.zeros((1, len(heads), Tq, Tk), dtype=np.uint8)      # oracle mask of the compared heads
+    reports = []
+    try:
+        for t in range(steps):
+            thr = thresholds[t] if thresholds is not None else threshold
+            q, k, v = (x.to(dev).contiguous() for x in next(seq))
+            if layout == "bnhd":
+                mem = [x.permute(0, 2, 1, 3).contiguous() for x in (q, k, v)]
+                out_mem = torch.empty_like(mem[0])
+                out = out_mem.permute(0, 2, 1, 3)
+            else:
+                mem = [q, k, v]
+                out_mem = out = torch.empty_like(q)
+            qs, ks, vs = (inputs.bf16_bits(x.reshape(B * H, N, d)[heads].unsqueeze(0)) for x in (q, k, v))
+            # teacher forcing: compared rows of the HIP mask := oracle's entry mask
+            if t > 0:
+                bits = la.lite_attn_mask_export(handle).reshape(B * H * Tq, W)
+                bits[rows] = pack_mask(m_ref.reshape(-1, Tk)[sub_rows])
+                la.lite_attn_mask_import(handle, bits, t)
+            la.lite_attn_fwd(mem[0].data_ptr(), mem[1].data_ptr(), mem[2].data_ptr(), out_mem.data_ptr(), handle,
+                             thr, t)
+            torch.cuda.synchronize()
+            o_ref, m_new, g = oracle_step(qs, ks, vs, m_ref, thr, protect=wl.protect, rows=sub_rows)
+            o_gpu = out.reshape(B * H, N, d)[heads].float().cpu().numpy()
+            m_gpu = unpack_mask(la.lite_attn_mask_export(handle).reshape(B * H * Tq, W), Tk)[rows]
+            sel_o = np.zeros((len(heads), N), dtype=bool)
+            for r in sub_rows:
+                sel_o[r // Tq, (r % Tq) * 128:min(N, (r % Tq + 1) * 128)] = True
+            rep = check_step(o_gpu[sel_o], o_ref[0][sel_o], m_gpu, m_new.reshape(-1, Tk)[sub_rows],
+                             g.reshape(-1, Tk)[sub_rows], thr)
+            st = la.lite_attn_skip_stats(handle, t)
+            rep.update(step=t, threshold=thr, gpu_skipped_in=st.tiles_skipped_in / st.tiles_total,
+                       gpu_newly=st.tiles_newly_marked / st.tiles_total)
+            if verbose:
+                print("step %d thr %.2f: max|dO| %.2e (max|O| %.2f) mean|dO| %.2e, skipped-out %.3f, excused %d" % (
+                    t, thr, rep["max_dO"], rep["max_O"], rep["mean_dO"], rep["skipped_out"], rep["mask_excused"]),
+                    flush=True)
+            reports.append(rep)
+            m_ref = m_new
+    finally:
+        la.lite_attn_free_mask(handle)
+    return reports

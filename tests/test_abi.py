@@ -1,0 +1,64 @@
+"""CPU checks of the C-ABI library: it loads, exports every symbol the header declares, and rejects bad
+arguments before touching the GPU (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "lite_attn.h")
+LIB = os.path.join(ROOT, "paper_2511_11062_amd", "liblite_attn.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        import __graft_entry__
+        __graft_entry__.build()
+    return ctypes.CDLL(LIB)
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lite_attn_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_named_entry_points():
+    names = declared_functions()
+    for n in ("lite_attn_init_mask", "lite_attn_fwd", "lite_attn_skip_stats"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    from paper_2511_11062_amd import lite_attn as la
+    ok = dict(batch=1, heads=2, seqlen=256)
+    h = ctypes.c_void_p()
+    assert lib.lite_attn_init_mask(None, ctypes.byref(h)) == -1
+    def rc(**kw):
+        args = dict(ok); args.update(kw)
+        strides = args.pop("strides", (args["heads"] * args["seqlen"] * 128, args["seqlen"] * 128, 128))
+        d = la.Desc(args["batch"], args["heads"], args["seqlen"], args.get("head_dim", 128), args.get("tile_q", 128),
+                    args.get("tile_k", 128), strides[0], strides[1], strides[2], args.get("ps", 0), args.get("pl", 0),
+                    args.get("flags", 0), args.get("max_steps", 4))
+        return lib.lite_attn_init_mask(ctypes.byref(d), ctypes.byref(h))
+    assert rc(batch=0) == -1 and rc(seqlen=0) == -1 and rc(max_steps=0) == -1 and rc(flags=1) == -1
+    assert rc(strides=(0, 100, 128)) == -1            # stride not a multiple of 8 elements
+    assert rc(strides=(65536, 0, 128)) == -1          # two heads on top of each other
+    assert rc(pl=10, ps=250) == -1                    # protected range past the end
+    assert rc(head_dim=64) == -3 and rc(tile_q=64) == -3 and rc(tile_k=176) == -3
+    assert rc(seqlen=128 * 70000) == -3
+    assert h.value is None
+    # calls on a null handle
+    assert lib.lite_attn_fwd(None, None, None, None, None, ctypes.c_float(-1.0), 0) == -1
+    assert lib.lite_attn_skip_stats(None, 0, None) == -1
+    assert lib.lite_attn_mask_words(None) == 0
+    lib.lite_attn_free_mask(None)
+    lib.lite_attn_strerror.restype = ctypes.c_char_p
+    assert b"step" in lib.lite_attn_strerror(-2)

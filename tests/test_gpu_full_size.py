@@ -1,0 +1,32 @@
+"""Parity at the benchmark's full shapes, in the launch configuration bench.py times, on sampled Q-tile rows
+(rows are independent, so the oracle computes exactly those rows over all K/V of their heads)."""
+import pytest
+
+import parity
+
+pytestmark = pytest.mark.gpu
+NINF = -float("inf")
+
+
+def test_wan13b_dense_equals_softmax_attention():
+    """Config 2: B=1,H=12,N=32760, empty mask, threshold disabled."""
+    reps = parity.run_sequence_check("wan1.3b_dense", steps=1, threshold=NINF, sample_rows=12, verbose=True)
+    assert reps[0]["skipped_out"] == 0.0 and reps[0]["gpu_newly"] == 0.0
+
+
+def test_wan13b_sweep_three_steps():
+    """Config 3 shape, three steps with a fixed threshold."""
+    reps = parity.run_sequence_check("wan1.3b_sweep", steps=3, threshold=-3.0, sample_rows=12, verbose=True)
+    assert reps[-1]["skipped_out"] > 0.1
+
+
+def test_wan14b_two_steps():
+    """Config 4: B=1,H=40,N=75600 (tail tile of 80 columns)."""
+    reps = parity.run_sequence_check("wan14b", steps=2, threshold=-3.0, sample_rows=10, verbose=True)
+    assert reps[-1]["skipped_out"] > 0.1
+
+
+def test_longvideo_with_text_tokens_two_steps():
+    """Config 5: B=1,H=24,N=118800+256 text tokens (931x931 tiles, tail tile of 16 columns, protected range)."""
+    reps = parity.run_sequence_check("longvideo", steps=2, threshold=-3.0, sample_rows=8, verbose=True)
+    assert reps[-1]["skipped_out"] > 0.1

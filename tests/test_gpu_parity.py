@@ -1,0 +1,117 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import parity
+from paper_2511_11062_amd import inputs
+
+pytestmark = pytest.mark.gpu
+NINF = -float("inf")
+
+
+def small(name, heads, grid, steps, text=0, batch=1, seed=5):
+    return inputs.Workload(name, batch, heads, grid, text_tokens=text, steps=steps, seed=seed)
+
+
+def test_tiny_config_full_parity_four_steps():
+    """Benchmark config 1: B=1,H=2,N=2048,d=128, 4 steps, fixed threshold, every row compared."""
+    reps = parity.run_sequence_check("tiny", steps=4, threshold=-2.0, verbose=True)
+    assert reps[0]["gpu_skipped_in"] == 0.0 and reps[0]["gpu_newly"] > 0.2
+    assert reps[-1]["skipped_out"] >= reps[0]["skipped_out"] > 0.2
+
+
+def test_rising_thresholds_grow_the_mask():
+    reps = parity.run_sequence_check("tiny", steps=4, thresholds=[-3.5, -3.0, -2.0, -1.0], verbose=True)
+    frac = [r["skipped_out"] for r in reps]
+    assert frac == sorted(frac) and frac[-1] > frac[0]
+    for a, b in zip(reps[:-1], reps[1:]):
+        assert abs(b["gpu_skipped_in"] - a["skipped_out"]) < 1e-12   # teacher-forced entry mask = oracle's exit mask
+
+
+@pytest.mark.parametrize("layout", ["bhnd", "bnhd"])
+@pytest.mark.parametrize("n_grid", [(1, 1, 1), (1, 5, 17), (1, 8, 16), (3, 10, 30), (2, 24, 31)])
+def test_dense_ragged_shapes(n_grid, layout):
+    """Threshold disabled: the result is dense softmax attention (paper eqs. 1-3); N = 1, 85, 128, 900, 1488."""
+    wl = small("ragged", 3, n_grid, 1, batch=2)
+    reps = parity.run_sequence_check(wl, steps=1, threshold=NINF, layout=layout)
+    assert reps[0]["skipped_out"] == 0.0 and reps[0]["gpu_newly"] == 0.0
+
+
+def test_ragged_multi_step_with_skips():
+    """N = 1488 = 11 full tiles + a 80-column tail, three steps with skipping."""
+    wl = small("ragged_seq", 2, (2, 24, 31), 3)
+    reps = parity.run_sequence_check(wl, steps=3, thresholds=[-3.0, -2.0, -1.5], verbose=True)
+    assert reps[-1]["skipped_out"] > 0.05
+
+
+def test_protected_text_tokens_are_never_skipped():
+    """Video grid of 1100 tokens + 150 text tokens (range 1100..1249 straddles tiles 8 and 9)."""
+    wl = small("text", 2, (2, 22, 25), 3, text=150)
+    reps = parity.run_sequence_check(wl, steps=3, thresholds=[-2.5, -1.5, -0.5], verbose=True)
+    assert reps[-1]["skipped_out"] > 0.05
+
+
+def test_skiplist_compaction_matches_host_reference():
+    from paper_2511_11062_amd import lite_attn as la
+    rng = np.random.default_rng(3)
+    for (B, H, N) in [(1, 2, 2048), (2, 3, 128 * 70 + 5), (1, 1, 128 * 200)]:
+        Tq = Tk = -(-N // 128)
+        h = la.lite_attn_init_mask(B, H, N)
+        try:
+            for density in (0.0, 0.3, 0.9, 1.0):
+                mask = (rng.random((B * H * Tq, Tk)) < density).astype(np.uint8)
+                la.lite_attn_mask_import(h, parity.pack_mask(mask), 1)
+                idx, cnt = la.lite_attn_skiplist_export(h, B * H * Tq, Tk)
+                assert np.array_equal(cnt, (mask == 0).sum(axis=1))
+                for r in range(B * H * Tq):
+                    assert np.array_equal(idx[r, :cnt[r]], np.flatnonzero(mask[r] == 0))
+                assert np.array_equal(parity.unpack_mask(la.lite_attn_mask_export(h).reshape(-1, -(-Tk // 64)), Tk), mask)
+        finally:
+            la.lite_attn_free_mask(h)
+
+
+def test_step_protocol_and_argument_errors():
+    from paper_2511_11062_amd import lite_attn as la
+    h = la.lite_attn_init_mask(1, 1, 256, max_steps=3)
+    x = torch.zeros(1, 1, 256, 128, dtype=torch.bfloat16, device="cuda")
+    o = torch.empty_like(x)
+    try:
+        for bad_thr in (0.0, 1.0, float("nan")):
+            with pytest.raises(la.LiteAttnError) as e:
+                la.lite_attn_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), o.data_ptr(), h, bad_thr, 0)
+            assert e.value.code == -1
+        with pytest.raises(la.LiteAttnError) as e:
+            la.lite_attn_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), o.data_ptr(), h, -1.0, 1)   # no step 0 yet
+        assert e.value.code == -2
+        with pytest.raises(la.LiteAttnError):
+            la.lite_attn_fwd(x.data_ptr() + 2, x.data_ptr(), x.data_ptr(), o.data_ptr(), h, -1.0, 0)  # misaligned
+        la.lite_attn_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), o.data_ptr(), h, -1.0, 0)
+        la.lite_attn_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), o.data_ptr(), h, -1.0, 1)
+        with pytest.raises(la.LiteAttnError):
+            la.lite_attn_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), o.data_ptr(), h, -1.0, 3)   # skipped a step
+        la.lite_attn_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), o.data_ptr(), h, -1.0, 2)
+        with pytest.raises(la.LiteAttnError):
+            la.lite_attn_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), o.data_ptr(), h, -1.0, 3)   # >= max_steps
+        torch.cuda.synchronize()
+        assert torch.equal(o, torch.zeros_like(o))          # all-zero V
+        st = la.lite_attn_skip_stats(h, 2)
+        assert st.tiles_total == 4
+    finally:
+        la.lite_attn_free_mask(h)
+
+
+def test_fully_masked_row_gives_zero_output():
+    """Only reachable through import (the method itself always keeps the first live tile of a row)."""
+    from paper_2511_11062_amd import lite_attn as la
+    h = la.lite_attn_init_mask(1, 1, 256, max_steps=4)
+    x = torch.randn(1, 1, 256, 128, device="cuda").to(torch.bfloat16)
+    o = torch.full_like(x, 7.0)
+    try:
+        la.lite_attn_mask_import(h, parity.pack_mask(np.array([[1, 1], [0, 1]], dtype=np.uint8)), 1)
+        la.lite_attn_fwd(x.data_ptr(), x.data_ptr(), x.data_ptr(), o.data_ptr(), h, -1.0, 1)
+        torch.cuda.synchronize()
+        assert torch.equal(o[0, 0, :128], torch.zeros_like(o[0, 0, :128]))
+        assert torch.isfinite(o).all() and o[0, 0, 128:].abs().max() > 0
+    finally:
+        la.lite_attn_free_mask(h)
