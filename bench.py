@@ -1,0 +1,144 @@
+#!/usr/bin/env python3
+"""Benchmark of the LiteAttention hot path on one MI355X.
+
+A "step" is one denoising timestep of one attention layer: one lite_attn_fwd call (Skip-List compaction +
+fused skip-aware attention) over one set of synthetic Q, K, V already resident in HBM.  The timed region is
+the first K steps of a fresh trajectory (step 0 starts from an empty Skip-Mask, i.e. the dense path; later
+steps skip what earlier steps marked).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload wan14b] [--threshold T]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+TILE_FLOP = 4.0 * 128 * 128 * 128          # QK^T + PV of one live 128x128 tile pair, d = 128
+PEAK_BF16_TFLOPS = 2500.0                  # MI355X dense bf16 MFMA, published
+
+# skip threshold (natural-log units of S) used per workload when none is given
+DEFAULT_THRESHOLD = {"tiny": -2.0, "wan1.3b_dense": -float("inf"), "wan1.3b_sweep": -3.0, "wan14b": -3.0,
+                     "longvideo": -3.0}
+
+
+def cpu_baseline(wl, q, k, v, threshold, budget_rows):
+    """Times the CPU oracle, as it stands, on a sample of Q-tile rows of step 0 (dense: empty mask)."""
+    import numpy as np
+    from oracle import lite_attn_oracle as orc
+    from paper_2511_11062_amd import inputs
+    N, d = wl.seqlen, wl.head_dim
+    Tq = -(-N // 128)
+    cores = orc.threads()
+    nrows = min(budget_rows, Tq)
+    rows = sorted(set(int(x) for x in np.linspace(0, Tq - 1, nrows)))            # head 0 only
+    qs, ks, vs = (inputs.bf16_bits(x[:1, :1]) for x in (q, k, v))
+    mask = np.zeros((1, 1, Tq, Tq), dtype=np.uint8)
+    orc.oracle_step(qs, ks, vs, mask, threshold, protect=wl.protect, rows=rows[:1])     # load + page in
+    t0 = time.perf_counter()
+    orc.oracle_step(qs, ks, vs, mask, threshold, protect=wl.protect, rows=rows)
+    dt = time.perf_counter() - t0
+    valid = sum(min(128, N - r * 128) for r in rows)
+    flops = 4.0 * valid * N * d
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s (dense-equivalent)", "cores": cores, "kind": "oracle",
+            "sample": "%d of %d Q-tile rows of step 0 (empty mask) of head 0 over all %d K/V tiles, %.1f s, "
+                      "extrapolated per row" % (len(rows), wl.batch * wl.heads * Tq, Tq, dt),
+            "ms_per_step_extrapolated": dt / len(rows) * wl.batch * wl.heads * Tq * 1e3}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="wan14b")
+    ap.add_argument("--threshold", type=float, default=None)
+    ap.add_argument("--cpu-rows", type=int, default=None, help="Q-tile rows the oracle baseline runs (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (heads shard across GPUs with no collective; see DESIGN.md); "
+                 "--gpus %d is not supported" % args.gpus)
+
+    import torch
+    from paper_2511_11062_amd import inputs
+    from paper_2511_11062_amd import lite_attn as la
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    wl = inputs.WORKLOADS[args.workload]
+    thr = DEFAULT_THRESHOLD[args.workload] if args.threshold is None else args.threshold
+    K, W = args.steps, args.warmup
+    dev = torch.device("cuda:0")
+    B, H, N, d = wl.batch, wl.heads, wl.seqlen, wl.head_dim
+    Tq = -(-N // 128)
+
+    seq = inputs.DriftSequence(wl, dev)
+    data = [next(seq) for _ in range(K)]                    # K steps of bf16 (q,k,v), resident in HBM
+    del seq
+    out = torch.empty_like(data[0][0])
+    handle = la.lite_attn_init_mask(B, H, N, protect=wl.protect, max_steps=max(K, W, 1))
+    la.lite_attn_set_stream(handle, torch.cuda.current_stream().cuda_stream)
+    la.lite_attn_profile(handle, True)
+
+    def run(steps):
+        for t in range(steps):
+            q, k, v = data[t % K]
+            la.lite_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), handle, thr, t)
+
+    run(W)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(K)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    per_step = []
+    live_flop = 0.0
+    fwd_ms_total = 0.0
+    for t in range(K):
+        st = la.lite_attn_skip_stats(handle, t)
+        cms, fms = la.lite_attn_kernel_times(handle, t)
+        live = st.tiles_total - st.tiles_skipped_in
+        live_flop += live * TILE_FLOP
+        fwd_ms_total += fms
+        per_step.append({"step": t, "skip_ratio": round(st.tiles_skipped_in / st.tiles_total, 4),
+                         "newly_marked": round(st.tiles_newly_marked / st.tiles_total, 4),
+                         "compact_ms": round(cms, 4), "attn_ms": round(fms, 3),
+                         "attn_tflops_live": round(live * TILE_FLOP / fms / 1e9, 1)})
+    la.lite_attn_free_mask(handle)
+
+    dense = wl.dense_flops()
+    achieved = live_flop / (fwd_ms_total * 1e-3) / 1e12
+    result = {
+        "metric": "dense-equivalent attention TFLOP/s over a denoising sequence (4*B*H*N^2*d per step / time)",
+        "value": round(K * dense / wall / 1e12, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(wall / K * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: B=%d H=%d N=%d d=%d, %dx%dx%d latent grid%s, steps 0..%d of a drift sequence" % (
+            wl.name, B, H, N, d, wl.grid[0], wl.grid[1], wl.grid[2],
+            " + %d protected text tokens" % wl.text_tokens if wl.text_tokens else "", K - 1),
+            "threshold": thr, "mask_tile": "128x128",
+            "mean_skip_ratio": round(sum(s["skip_ratio"] for s in per_step) / K, 4)},
+        "dense_step": {"ms": per_step[0]["attn_ms"], "tflops": per_step[0]["attn_tflops_live"],
+                       "frac_of_bf16_peak": round(per_step[0]["attn_tflops_live"] / PEAK_BF16_TFLOPS, 4)},
+        "per_step": per_step,
+        "roofline": {"bound": "mfma", "kernel": "lite_attn_fwd_kernel", "achieved": round(achieved, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None,
+                     "note": "achieved = 8.39 MFLOP x live tiles of the K timed launches / their summed HIP-event "
+                             "durations"},
+    }
+    rows = args.cpu_rows
+    if rows is None:
+        from oracle import lite_attn_oracle as orc
+        # about 10-30 s of oracle time: one row-step costs 4*128*N*d flop at roughly 6 GFLOP/s per core
+        per_row_s = 4.0 * 128 * N * d / 6.0e9
+        rows = max(1, min(Tq, int(20.0 / per_row_s * orc.threads())))
+    if rows > 0:
+        result["cpu_baseline"] = cpu_baseline(wl, data[0][0], data[0][1], data[0][2], thr, rows)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

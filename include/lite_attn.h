@@ -89,6 +89,13 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
    Synchronises the handle's stream. */
 int lite_attn_skip_stats(lite_attn_mask_t* mask, int step, lite_attn_stats_t* host_out);
 
+/* Per-kernel timing for benchmarks.  enable != 0 makes every later lite_attn_fwd record HIP events on the handle's
+   stream around its two kernels (events are created on the first enabled call; a few microseconds per call).
+   lite_attn_kernel_times returns the durations of a completed step in milliseconds; it synchronises the stream
+   and fails with LITE_ATTN_ESTEP if that step was not run with profiling enabled. */
+int lite_attn_profile(lite_attn_mask_t* mask, int enable);
+int lite_attn_kernel_times(lite_attn_mask_t* mask, int step, float* host_compact_ms, float* host_fwd_ms);
+
 /* Number of uint64 words of the whole mask: B*H*Tq*ceil(Tk/64). */
 size_t lite_attn_mask_words(const lite_attn_mask_t* mask);
 

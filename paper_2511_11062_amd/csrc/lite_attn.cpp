@@ -19,6 +19,9 @@ struct lite_attn_mask {
   unsigned long long* d_stats;  // [max_steps][2]: skipped on entry, newly marked
   hipStream_t stream;
   int next_step;
+  bool profile;
+  hipEvent_t* events;  // [max_steps][3] once profiling was enabled: before compaction, between, after attention
+  bool* timed;         // [max_steps]
 };
 
 namespace {
@@ -74,6 +77,9 @@ int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out) {
   m->rows = (int64_t)desc->batch * desc->heads * m->Tq;
   m->stream = nullptr;
   m->next_step = 0;
+  m->profile = false;
+  m->events = nullptr;
+  m->timed = nullptr;
   m->d_bits = nullptr; m->d_live_idx = nullptr; m->d_live_cnt = nullptr; m->d_stats = nullptr;
   hipError_t e = hipMalloc(&m->d_bits, sizeof(uint64_t) * (size_t)m->rows * m->W);
   if (e == hipSuccess) e = hipMalloc(&m->d_live_idx, sizeof(uint16_t) * (size_t)m->rows * m->Tk);
@@ -109,6 +115,9 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
   if (step == 0)
     LA_HIP(la::launch_clear(m->d_bits, (size_t)m->rows * m->W, m->d_stats, 2 * (size_t)d.max_steps, m->stream));
   unsigned long long* st = m->d_stats + 2 * (size_t)step;
+  hipEvent_t* ev = (m->profile && m->events) ? m->events + 3 * (size_t)step : nullptr;
+  if (m->timed) m->timed[step] = ev != nullptr;
+  if (ev) LA_HIP(hipEventRecord(ev[0], m->stream));
   LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->d_live_idx, m->d_live_cnt, st, m->stream));
   la::FwdParams p;
   p.q = static_cast<const uint16_t*>(q);
@@ -124,7 +133,9 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
   p.protect_start = d.protect_start; p.protect_len = d.protect_len;
   p.rows_total = (int)m->rows;
   p.rows_per_xcd = (int)((m->rows + 7) / 8);
+  if (ev) LA_HIP(hipEventRecord(ev[1], m->stream));
   LA_HIP(la::launch_fwd(p, m->stream));
+  if (ev) LA_HIP(hipEventRecord(ev[2], m->stream));
   m->next_step = step + 1;
   return LITE_ATTN_OK;
 }
@@ -140,6 +151,43 @@ int lite_attn_skip_stats(lite_attn_mask_t* m, int step, lite_attn_stats_t* host_
   host_out->tiles_skipped_in = raw[0];
   host_out->tiles_newly_marked = raw[1];
   host_out->live_list_bytes = (host_out->tiles_total - raw[0]) * sizeof(uint16_t);
+  return LITE_ATTN_OK;
+}
+
+int lite_attn_profile(lite_attn_mask_t* m, int enable) {
+  if (!m) return LITE_ATTN_EINVAL;
+  if (enable && !m->events) {
+    const size_t n = 3 * (size_t)m->desc.max_steps;
+    hipEvent_t* ev = new (std::nothrow) hipEvent_t[n];
+    bool* timed = new (std::nothrow) bool[m->desc.max_steps]();
+    if (!ev || !timed) {
+      delete[] ev;
+      delete[] timed;
+      return LITE_ATTN_ENOMEM;
+    }
+    for (size_t x = 0; x < n; ++x) {
+      hipError_t e = hipEventCreate(&ev[x]);
+      if (e != hipSuccess) {
+        for (size_t y = 0; y < x; ++y) (void)hipEventDestroy(ev[y]);
+        delete[] ev;
+        delete[] timed;
+        return hip_fail(e);
+      }
+    }
+    m->events = ev;
+    m->timed = timed;
+  }
+  m->profile = enable != 0;
+  return LITE_ATTN_OK;
+}
+
+int lite_attn_kernel_times(lite_attn_mask_t* m, int step, float* host_compact_ms, float* host_fwd_ms) {
+  if (!m || !host_compact_ms || !host_fwd_ms) return LITE_ATTN_EINVAL;
+  if (step < 0 || step >= m->desc.max_steps || !m->events || !m->timed[step]) return LITE_ATTN_ESTEP;
+  hipEvent_t* ev = m->events + 3 * (size_t)step;
+  LA_HIP(hipEventSynchronize(ev[2]));
+  LA_HIP(hipEventElapsedTime(host_compact_ms, ev[0], ev[1]));
+  LA_HIP(hipEventElapsedTime(host_fwd_ms, ev[1], ev[2]));
   return LITE_ATTN_OK;
 }
 
@@ -178,6 +226,11 @@ void lite_attn_free_mask(lite_attn_mask_t* m) {
   if (m->d_live_idx) (void)hipFree(m->d_live_idx);
   if (m->d_live_cnt) (void)hipFree(m->d_live_cnt);
   if (m->d_stats) (void)hipFree(m->d_stats);
+  if (m->events) {
+    for (size_t x = 0; x < 3 * (size_t)m->desc.max_steps; ++x) (void)hipEventDestroy(m->events[x]);
+    delete[] m->events;
+  }
+  delete[] m->timed;
   delete m;
 }
 

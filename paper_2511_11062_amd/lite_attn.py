@@ -48,12 +48,15 @@ _lib.lite_attn_mask_words.restype = ctypes.c_size_t
 _lib.lite_attn_mask_export.argtypes = [_H, ctypes.c_void_p, ctypes.c_size_t]
 _lib.lite_attn_mask_import.argtypes = [_H, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
 _lib.lite_attn_skiplist_export.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p]
+_lib.lite_attn_profile.argtypes = [_H, ctypes.c_int]
+_lib.lite_attn_kernel_times.argtypes = [_H, ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
 _lib.lite_attn_free_mask.argtypes = [_H]
 _lib.lite_attn_free_mask.restype = None
 _lib.lite_attn_strerror.argtypes = [ctypes.c_int]
 _lib.lite_attn_strerror.restype = ctypes.c_char_p
 _lib.lite_attn_last_hip_error.restype = ctypes.c_int
-for _n in ("init_mask", "set_stream", "fwd", "skip_stats", "mask_export", "mask_import", "skiplist_export"):
+for _n in ("init_mask", "set_stream", "fwd", "skip_stats", "mask_export", "mask_import", "skiplist_export",
+           "profile", "kernel_times"):
     getattr(_lib, "lite_attn_" + _n).restype = ctypes.c_int
 
 
@@ -122,6 +125,17 @@ def lite_attn_skiplist_export(mask, rows: int, tk: int):
     cnt = np.empty(rows, dtype=np.uint32)
     _check(_lib.lite_attn_skiplist_export(mask, idx.ctypes.data, cnt.ctypes.data))
     return idx, cnt
+
+
+def lite_attn_profile(mask, enable: bool):
+    _check(_lib.lite_attn_profile(mask, 1 if enable else 0))
+
+
+def lite_attn_kernel_times(mask, step):
+    """-> (compaction_ms, attention_ms) of a completed step that ran with profiling enabled."""
+    a, b = ctypes.c_float(), ctypes.c_float()
+    _check(_lib.lite_attn_kernel_times(mask, int(step), ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
 
 
 def lite_attn_free_mask(mask):
