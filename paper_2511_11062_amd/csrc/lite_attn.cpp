@@ -12,10 +12,12 @@
 struct lite_attn_mask {
   lite_attn_desc_t desc;
   int Tq, Tk, W;
+  int live_stride;  // uint16 entries per Skip-List row (Tk rounded up to even)
   int64_t rows;
   uint64_t* d_bits;
   uint16_t* d_live_idx;
   uint32_t* d_live_cnt;
+  uint16_t* d_vt;  // V^T scratch of the current call: [B*H][128][128*Tk] bf16
   unsigned long long* d_stats;  // [max_steps][2]: skipped on entry, newly marked
   hipStream_t stream;
   int next_step;
@@ -55,6 +57,8 @@ int check_desc(const lite_attn_desc_t* d) {
   if (d->head_dim != 128 || d->tile_q != 128 || d->tile_k != 128) return LITE_ATTN_EUNSUPPORTED;
   const int64_t Tk = ((int64_t)d->seqlen + 127) / 128;
   if (Tk > 65535) return LITE_ATTN_EUNSUPPORTED;
+  // K/V stages are addressed with 32-bit byte offsets from the head's base pointer
+  if (((int64_t)d->seqlen + 128) * d->stride_n * 2 >= ((int64_t)1 << 32)) return LITE_ATTN_EUNSUPPORTED;
   const int64_t rows = (int64_t)d->batch * d->heads * Tk;
   if (rows > (int64_t)1 << 30) return LITE_ATTN_EUNSUPPORTED;
   return LITE_ATTN_OK;
@@ -74,16 +78,19 @@ int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out) {
   m->Tq = (desc->seqlen + desc->tile_q - 1) / desc->tile_q;
   m->Tk = (desc->seqlen + desc->tile_k - 1) / desc->tile_k;
   m->W = (m->Tk + 63) / 64;
+  m->live_stride = (m->Tk + 1) & ~1;
   m->rows = (int64_t)desc->batch * desc->heads * m->Tq;
   m->stream = nullptr;
   m->next_step = 0;
   m->profile = false;
   m->events = nullptr;
   m->timed = nullptr;
-  m->d_bits = nullptr; m->d_live_idx = nullptr; m->d_live_cnt = nullptr; m->d_stats = nullptr;
+  m->d_bits = nullptr; m->d_live_idx = nullptr; m->d_live_cnt = nullptr; m->d_stats = nullptr; m->d_vt = nullptr;
   hipError_t e = hipMalloc(&m->d_bits, sizeof(uint64_t) * (size_t)m->rows * m->W);
-  if (e == hipSuccess) e = hipMalloc(&m->d_live_idx, sizeof(uint16_t) * (size_t)m->rows * m->Tk);
+  if (e == hipSuccess) e = hipMalloc(&m->d_live_idx, sizeof(uint16_t) * (size_t)m->rows * m->live_stride);
   if (e == hipSuccess) e = hipMalloc(&m->d_live_cnt, sizeof(uint32_t) * (size_t)m->rows);
+  if (e == hipSuccess)
+    e = hipMalloc(&m->d_vt, sizeof(uint16_t) * (size_t)desc->batch * desc->heads * 128 * ((size_t)m->Tk * 128));
   if (e == hipSuccess) e = hipMalloc(&m->d_stats, sizeof(unsigned long long) * 2 * (size_t)desc->max_steps);
   if (e == hipSuccess) e = la::prepare_fwd();
   if (e == hipSuccess)
@@ -118,15 +125,18 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
   hipEvent_t* ev = (m->profile && m->events) ? m->events + 3 * (size_t)step : nullptr;
   if (m->timed) m->timed[step] = ev != nullptr;
   if (ev) LA_HIP(hipEventRecord(ev[0], m->stream));
-  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->d_live_idx, m->d_live_cnt, st, m->stream));
+  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->live_stride, m->d_live_idx, m->d_live_cnt, st,
+                            m->stream));
+  LA_HIP(la::launch_transpose_v(static_cast<const uint16_t*>(v), m->d_vt, d.stride_b, d.stride_h, d.stride_n,
+                                d.batch * d.heads, d.heads, d.seqlen, m->Tk, m->stream));
   la::FwdParams p;
   p.q = static_cast<const uint16_t*>(q);
   p.k = static_cast<const uint16_t*>(k);
-  p.v = static_cast<const uint16_t*>(v);
+  p.vt = m->d_vt;
   p.out = static_cast<uint16_t*>(out);
   p.stride_b = d.stride_b; p.stride_h = d.stride_h; p.stride_n = d.stride_n;
   p.H = d.heads; p.N = d.seqlen; p.Tq = m->Tq; p.Tk = m->Tk; p.W = m->W;
-  p.live_idx = m->d_live_idx; p.live_cnt = m->d_live_cnt; p.bits = m->d_bits;
+  p.live_idx = m->d_live_idx; p.live_stride = m->live_stride; p.live_cnt = m->d_live_cnt; p.bits = m->d_bits;
   p.stat_newly = st + 1;
   p.thr = threshold;
   p.scale = 1.0f / std::sqrt((float)d.head_dim);
@@ -211,9 +221,11 @@ int lite_attn_mask_import(lite_attn_mask_t* m, const uint64_t* host_bits, size_t
 
 int lite_attn_skiplist_export(lite_attn_mask_t* m, uint16_t* host_live_idx, uint32_t* host_live_cnt) {
   if (!m || !host_live_idx || !host_live_cnt) return LITE_ATTN_EINVAL;
-  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->d_live_idx, m->d_live_cnt, nullptr, m->stream));
-  LA_HIP(hipMemcpyAsync(host_live_idx, m->d_live_idx, sizeof(uint16_t) * (size_t)m->rows * m->Tk,
-                        hipMemcpyDeviceToHost, m->stream));
+  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->live_stride, m->d_live_idx, m->d_live_cnt,
+                            nullptr, m->stream));
+  LA_HIP(hipMemcpy2DAsync(host_live_idx, sizeof(uint16_t) * (size_t)m->Tk, m->d_live_idx,
+                          sizeof(uint16_t) * (size_t)m->live_stride, sizeof(uint16_t) * (size_t)m->Tk, (size_t)m->rows,
+                          hipMemcpyDeviceToHost, m->stream));
   LA_HIP(hipMemcpyAsync(host_live_cnt, m->d_live_cnt, sizeof(uint32_t) * (size_t)m->rows, hipMemcpyDeviceToHost,
                         m->stream));
   LA_HIP(hipStreamSynchronize(m->stream));
@@ -226,6 +238,7 @@ void lite_attn_free_mask(lite_attn_mask_t* m) {
   if (m->d_live_idx) (void)hipFree(m->d_live_idx);
   if (m->d_live_cnt) (void)hipFree(m->d_live_cnt);
   if (m->d_stats) (void)hipFree(m->d_stats);
+  if (m->d_vt) (void)hipFree(m->d_vt);
   if (m->events) {
     for (size_t x = 0; x < 3 * (size_t)m->desc.max_steps; ++x) (void)hipEventDestroy(m->events[x]);
     delete[] m->events;

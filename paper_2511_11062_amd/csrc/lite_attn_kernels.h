@@ -9,11 +9,12 @@ namespace la {
 struct FwdParams {
   const uint16_t* q;
   const uint16_t* k;
-  const uint16_t* v;
+  const uint16_t* vt;                    // V^T scratch: [B*H][128][128*Tk], written by launch_transpose_v
   uint16_t* out;
   int64_t stride_b, stride_h, stride_n;  // elements
   int H, N, Tq, Tk, W;                   // W = uint64 words per mask row
-  const uint16_t* live_idx;              // [rows][Tk]
+  const uint16_t* live_idx;              // [rows][live_stride], live_stride even so that rows are 4-byte aligned
+  int live_stride;
   const uint32_t* live_cnt;              // [rows]
   uint64_t* bits;                        // [rows][W]
   unsigned long long* stat_newly;        // counter of the current step
@@ -26,8 +27,10 @@ struct FwdParams {
 int fwd_lds_bytes();
 hipError_t prepare_fwd();
 hipError_t launch_clear(uint64_t* bits, size_t words, unsigned long long* stats, size_t nstats, hipStream_t st);
-hipError_t launch_compact(const uint64_t* bits, int rows, int Tk, int W, uint16_t* live_idx, uint32_t* live_cnt,
-                          unsigned long long* stat_skipped_in, hipStream_t st);
+hipError_t launch_compact(const uint64_t* bits, int rows, int Tk, int W, int live_stride, uint16_t* live_idx,
+                          uint32_t* live_cnt, unsigned long long* stat_skipped_in, hipStream_t st);
+hipError_t launch_transpose_v(const uint16_t* v, uint16_t* vt, int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                              int BH, int H, int N, int Tk, hipStream_t st);
 hipError_t launch_fwd(const FwdParams& p, hipStream_t st);
 
 }  // namespace la

@@ -6,18 +6,21 @@
 //   lite_attn_fwd_kernel : fused tiled forward over the live tiles with the skip predicate
 //                          (Algorithm 2; eq. sparge_cond; tile recurrences of the Preliminaries)
 //
-// Layout of the fused kernel (one workgroup = one Q tile = one Skip-Mask row, 4 wave64s):
-//   * wave w owns Q rows [32w, 32w+32) of the tile; lane l owns Q row (l & 31) of them.
-//   * the kernel works on S^T = K Q^T: with v_mfma_f32_32x32x16_bf16 the K rows are the A operand (from
-//     LDS) and the Q rows the B operand (registers, loaded once), so a lane's 16 accumulator values per
-//     32x32 block all belong to ONE Q row.  Row max and row sum are then in-lane reductions plus one
-//     exchange with lane^32, and exp(S^T) in accumulator layout IS the B operand of O^T = V^T P^T:
-//     P never moves between lanes.
-//   * a 128-column mask tile is streamed as two 64-column stages; K is stored row-major (padded) in LDS,
-//     V is transposed in registers on its way into LDS so that V^T fragments are single 16-byte reads.
-//   * LDS is double-buffered (2 x 35 KB), one barrier per stage, two workgroups per CU.
-//   * the predicate of a tile is reduced per wave with a ballot; the four per-wave results meet through
-//     LDS at the barrier that ends the tile and one lane ORs the bit into the global mask row.
+// Fused kernel, one workgroup (4 wave64) = one Q tile = one Skip-Mask row:
+//   * wave w owns Q rows [32w, 32w+32); lane l owns Q row (l & 31) of them.
+//   * it works on S^T = K Q^T with v_mfma_f32_32x32x16_bf16: K rows are the A operand (LDS), Q rows the B
+//     operand (registers, loaded once), so the 16 accumulator values a lane holds per 32x32 block all belong
+//     to ONE Q row: row max / row sum are in-lane reductions plus one v_permlane32_swap, and exp(S^T) in
+//     accumulator layout IS the B operand of O^T = V^T P^T -- P never moves between lanes.
+//   * a 128-column mask tile is streamed as two 64-column stages.  K and V stages go global -> LDS with
+//     buffer_load ... lds (no registers, rows past the end of the sequence arrive as zeros through the buffer
+//     descriptor's range check); both are stored unpadded with an XOR swizzle applied on the global-address
+//     side.  K fragments are 16-byte LDS reads, V^T fragments are ds_read_b64_tr_b16 transposing reads.
+//   * software pipeline: in stage s the matrix cores run S(s+1) = K(s+1) Q^T and O += V(s-1) P(s-1) while the
+//     vector ALU runs the online softmax of stage s; LDS holds two K and two V stages (64 KB), one barrier per
+//     stage, two workgroups per CU.
+//   * the predicate of a tile is reduced per wave with a ballot; the four per-wave results meet through LDS
+//     at the barrier that ends the tile and one lane ORs the bit into the global mask row.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -26,20 +29,23 @@
 namespace la {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kD = 128;           // head dimension
+#define LA_LDS __attribute__((address_space(3)))
+
 constexpr int kTile = 128;        // Skip-Mask tile: 128 Q rows x 128 K/V columns
 constexpr int kSub = 64;          // K/V columns per pipeline stage
-constexpr int kThreads = 256;
-constexpr int kKRow = 272;        // bytes per K row in LDS: 128 bf16 + 16 B pad (conflict-free 16 B reads)
-constexpr int kVtRow = 144;       // bytes per V^T row in LDS: 64 bf16 + 16 B pad
-constexpr int kKBytes = kSub * kKRow;      // 17408
-constexpr int kVtBytes = kD * kVtRow;      // 18432
-constexpr int kStage = kKBytes + kVtBytes; // 35840
-constexpr int kFlagsOff = 2 * kStage;      // 8 ints: [tile parity][wave]
+constexpr int kStageBytes = kSub * 256;  // one K or V stage: 64 rows x 128 bf16, unpadded
+constexpr int kKOff = 0;                 // K stage p at kKOff + p * kStageBytes
+constexpr int kVOff = 2 * kStageBytes;   // V stage p at kVOff + p * kStageBytes
+constexpr int kFlagsOff = 4 * kStageBytes;  // 8 ints [tile parity][wave] + 64 dummy ints
+constexpr int kLdsBytes = kFlagsOff + 8 * 4 + 64 * 4;
 constexpr int kORow = 272;        // bytes per O row in the epilogue staging (reuses the stage buffers)
 
 __global__ void clear_state_kernel(uint64_t* bits, size_t words, unsigned long long* stats, size_t nstats) {
@@ -51,14 +57,14 @@ __global__ void clear_state_kernel(uint64_t* bits, size_t words, unsigned long l
 
 // One wave per Q-tile row: ballot + prefix popcount packs the indices of clear bits.
 __global__ __launch_bounds__(256) void compact_skiplist(const uint64_t* __restrict__ bits, int rows, int Tk, int W,
-                                                         uint16_t* __restrict__ live_idx,
+                                                         int live_stride, uint16_t* __restrict__ live_idx,
                                                          uint32_t* __restrict__ live_cnt,
                                                          unsigned long long* __restrict__ stat_skipped_in) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
   const uint64_t* mrow = bits + (size_t)row * W;
-  uint16_t* out = live_idx + (size_t)row * Tk;
+  uint16_t* out = live_idx + (size_t)row * live_stride;
   uint32_t n = 0;
   for (int w = 0; w < W; ++w) {
     const uint64_t word = mrow[w];
@@ -75,71 +81,304 @@ __global__ __launch_bounds__(256) void compact_skiplist(const uint64_t* __restri
   }
 }
 
-__device__ __forceinline__ uint4 ld16(const uint16_t* p) { return *reinterpret_cast<const uint4*>(p); }
-
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  typedef float f32x2 __attribute__((ext_vector_type(2)));
   f32x2 f = {a, b};
   bf16x2 h = __builtin_convertvector(f, bf16x2);
   return *reinterpret_cast<uint32_t*>(&h);
 }
 
-struct StageRegs {
-  uint4 k[4];
-  uint4 v[4];
+__device__ __forceinline__ float other_half_max(float x) {
+  // lanes l and l^32 exchange x; returns max(x, partner's x) in every lane
+  const uint32_t u = __float_as_uint(x);
+  const u32x2 sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+
+__device__ __forceinline__ float other_half_sum(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const u32x2 sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+}
+
+// V -> V^T pre-pass.  The PV product contracts over the K/V index, so the matrix cores want, per lane, 8 V values
+// of ONE feature d at 8 K/V positions: a 16-byte read from a [d][kv] layout, but a strided gather from V's [kv][d].
+// (gfx950's transposing LDS read, ds_read_b64_tr_b16, delivers only 8 bytes per lane and measured at a third of the
+// 16-byte read bandwidth, which made LDS the bound of the fused kernel.)  This kernel writes, once per call,
+// vt[bh][d][n_pad] with n_pad = 128 * Tk, zero beyond the sequence, with the K/V index permuted inside every
+// group of 16: position 8*h + t holds K/V offset 4*h + t + 4*(t >= 4) -- the order in which a lane of the fused
+// kernel holds its P~ values.  One workgroup transposes one 128 x 128 tile through LDS.
+__global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __restrict__ v, uint16_t* __restrict__ vt,
+                                                           int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                                                           int H, int N, int Tk) {
+  constexpr int kRow = 256 + 16;  // padded LDS row (bytes)
+  __shared__ __attribute__((aligned(16))) char tile[128 * kRow];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = blockIdx.x % Tk, bh = blockIdx.x / Tk;
+  const uint16_t* vb = v + (int64_t)(bh / H) * stride_b + (int64_t)(bh % H) * stride_h;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    const int r = (tid >> 4) + 16 * t, row = j * 128 + r;
+    uint4 x = {0u, 0u, 0u, 0u};
+    if (row < N) x = *reinterpret_cast<const uint4*>(vb + (int64_t)row * stride_n + 8 * (tid & 15));
+    *reinterpret_cast<uint4*>(tile + r * kRow + 16 * (tid & 15)) = x;
+  }
+  __syncthreads();
+  const int g = lane >> 4, i16 = lane & 15, r_src = i16 >> 2, c_src = lane & 3;
+  uint16_t* out = vt + (int64_t)bh * 128 * (128 * (int64_t)Tk) + (int64_t)j * 128;
+#pragma unroll
+  for (int x = 0; x < 8; ++x) {
+    const int q = 8 * wave + x;                    // 32 (16-group, half, d-half) combinations per tile
+    const int c16 = q >> 2, hh = (q >> 1) & 1, dhalf = q & 1;
+    const char* src = tile + (16 * c16 + 4 * hh + r_src) * kRow + 2 * (64 * dhalf + 16 * g + 4 * c_src);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LA_LDS s16x4*)(src));
+    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LA_LDS s16x4*)(src + 8 * kRow));
+    const s16x8 o = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+    const int d = 64 * dhalf + 16 * g + i16;
+    *reinterpret_cast<s16x8*>(out + (int64_t)d * (128 * (int64_t)Tk) + 16 * c16 + 8 * hh) = o;
+  }
+}
+
+// Geometry of the fused kernel: a wave owns QB blocks of 32 Q rows, a workgroup (one Q tile of 128 rows) has 4/QB waves.
+template <int QB>
+struct Geo {
+  static constexpr int kWaves = 4 / QB;
+  static constexpr int kThreads = 64 * kWaves;
+  static constexpr int kChunks = 16 / kWaves;  // 1 KB DMA pieces of a K (or V) stage per wave
 };
 
-// Global -> registers for one 64-column stage.  Rows past the end of the sequence read as zero.
-__device__ __forceinline__ void load_stage(StageRegs& r, const uint16_t* kb, const uint16_t* vb, int64_t stride_n,
-                                           int kv0, int N, int tid) {
-  const int lane = tid & 63, wave = tid >> 6;
-  const uint4 zero = {0u, 0u, 0u, 0u};
+// Per-lane constants of the fused kernel.
+template <int QB>
+struct Lane {
+  u32x4 krsrc, vrsrc;  // buffer descriptors of this head's K (range-checked: rows past the end read as 0) and V^T
+  uint32_t kdma[Geo<QB>::kChunks], vdma[Geo<QB>::kChunks];  // byte offsets (inside a stage) of this lane's DMA pieces
+  uint32_t kread[8];  // LDS byte offset of the K fragment for d-chunk kk (stage and block go into immediates)
+  uint32_t vread[4];  // LDS byte offset of the V^T fragment for column chunk cc (d-block via immediates)
+  uint32_t lds_wave;  // LDS address of this wave's first DMA piece inside stage buffer 0 (wave-uniform)
+  uint32_t stride2;   // stride_n * 2 (bytes per token row)
+  int hi;
+  bool qvalid[QB];
+  float c;            // scale * log2(e)
+  float scale, thr;
+  int N;
+};
+
+template <int QB>
+struct State {
+  bf16x8 qf[QB][8];
+  f32x16 oacc[QB][4];
+  f32x16 sA[QB][2], sB[QB][2];  // S^T of even / odd stages
+  uint32_t pw[QB][16];          // P~^T of the previous stage, bf16 pairs; words 4cc..4cc+3 = B operand of chunk cc
+  float m_run[QB], l_run[QB], mloc_tile[QB];
+};
+
+// Buffer descriptor (V#) of a raw buffer of `bytes` bytes at `ptr`: loads at offsets >= bytes return zero.
+__device__ __forceinline__ u32x4 make_rsrc(const void* ptr, uint32_t bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(ptr);
+  u32x4 r = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, bytes, 0x00020000u};
+  return r;
+}
+
+// One 1 KB piece global -> LDS without registers: lane l's 16 bytes land at lds_addr + 16*l.  Written as inline
+// assembly so that the compiler does not order later LDS reads of OTHER buffers behind this load (it would wait
+// for vmcnt(0) before every LDS read); completion is enforced by the s_waitcnt vmcnt(0) + barrier ending a stage.
+__device__ __forceinline__ void dma16(const u32x4 rsrc, uint32_t lds_addr, uint32_t voffset) {
+  asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
+               :
+               : "v"(voffset), "s"(rsrc), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+template <int QB>
+__device__ __forceinline__ void dma_stage(const u32x4 rsrc, const uint32_t* off, uint32_t stage_byte_base,
+                                          uint32_t lds_wave_addr) {
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int row = kv0 + (tid >> 4) + 16 * t;
-    r.k[t] = (row < N) ? ld16(kb + (int64_t)row * stride_n + 8 * (tid & 15)) : zero;
-  }
-  const int kg = lane & 15, dg = 4 * wave + (lane >> 4);
-#pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int row = kv0 + 4 * kg + t;
-    r.v[t] = (row < N) ? ld16(vb + (int64_t)row * stride_n + 8 * dg) : zero;
+  for (int x = 0; x < Geo<QB>::kChunks; ++x) {
+    dma16(rsrc, lds_wave_addr + 1024 * x, off[x] + stage_byte_base);
   }
 }
 
-// Registers -> LDS.  K goes in row-major; V is transposed 4x8 -> 8x4 in registers and written as V^T with the
-// K/V index permuted inside each group of 16 so that a lane's 8 contraction values are contiguous.
-__device__ __forceinline__ void store_stage(const StageRegs& r, char* stage, int tid) {
-  const int lane = tid & 63, wave = tid >> 6;
-  char* sK = stage;
-  char* sVt = stage + kKBytes;
+__device__ __forceinline__ bf16x8 p_operand(const uint32_t* w) {
+  const u32x4 v = {w[0], w[1], w[2], w[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// S^T(next) = K Q^T for one 64-column stage held in LDS at sK.
+template <int QB>
+__device__ __forceinline__ void mma_qk(f32x16 (&nxt)[QB][2], const bf16x8 (&qf)[QB][8], const char* sK,
+                                       const uint32_t (&kread)[8]) {
 #pragma unroll
-  for (int t = 0; t < 4; ++t)
-    *reinterpret_cast<uint4*>(sK + ((tid >> 4) + 16 * t) * kKRow + 16 * (tid & 15)) = r.k[t];
-  const int kg = lane & 15, dg = 4 * wave + (lane >> 4);
-  const int g = kg & 3;
-  const int pos = 32 * (kg >> 2) + ((g & 1) << 4) + ((g & 2) << 2);  // bytes: {0,16,8,24}[g]
-  const uint32_t v0[4] = {r.v[0].x, r.v[0].y, r.v[0].z, r.v[0].w};
-  const uint32_t v1[4] = {r.v[1].x, r.v[1].y, r.v[1].z, r.v[1].w};
-  const uint32_t v2[4] = {r.v[2].x, r.v[2].y, r.v[2].z, r.v[2].w};
-  const uint32_t v3[4] = {r.v[3].x, r.v[3].y, r.v[3].z, r.v[3].w};
+  for (int blk = 0; blk < 2; ++blk) {
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    uint2 lo, hi;
-    lo.x = __builtin_amdgcn_perm(v1[w], v0[w], 0x05040100u);
-    lo.y = __builtin_amdgcn_perm(v3[w], v2[w], 0x05040100u);
-    hi.x = __builtin_amdgcn_perm(v1[w], v0[w], 0x07060302u);
-    hi.y = __builtin_amdgcn_perm(v3[w], v2[w], 0x07060302u);
-    *reinterpret_cast<uint2*>(sVt + (8 * dg + 2 * w) * kVtRow + pos) = lo;
-    *reinterpret_cast<uint2*>(sVt + (8 * dg + 2 * w + 1) * kVtRow + pos) = hi;
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) nxt[qb][blk][r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(sK + 8192 * blk + kread[kk]);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+        nxt[qb][blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][kk], nxt[qb][blk], 0, 0, 0);
+    }
   }
 }
 
-__global__ __launch_bounds__(kThreads, 2) void lite_attn_fwd_kernel(const FwdParams p) {
+// O^T += V^T P~^T for one 64-column stage held in LDS at sV ([d][64 kv], 128-byte rows).
+template <int QB>
+__device__ __forceinline__ void mma_pv(f32x16 (&oacc)[QB][4], const uint32_t (&pw)[QB][16], const char* sV,
+                                       const uint32_t (&vread)[4]) {
+#pragma unroll
+  for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(sV + 4096 * db + vread[cc]);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+        oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_operand(&pw[qb][4 * cc]), oacc[qb][db], 0, 0, 0);
+    }
+}
+
+// LDS -> register fragment k of a stage's matrix work: k < 16 is the V^T fragment (column chunk k/4, d-block k%4)
+// of O^T += V^T P~^T, k >= 16 the K fragment (block (k-16)/8, d-chunk (k-16)%8) of S^T(s+1) = K Q^T.
+__device__ __forceinline__ bf16x8 load_frag(int k, const char* sK, const char* sV, const uint32_t (&kread)[8],
+                                            const uint32_t (&vread)[4]) {
+  if (k >= 16) return *reinterpret_cast<const bf16x8*>(sK + 8192 * ((k - 16) >> 3) + kread[k & 7]);
+  const int cc = k >> 2, db = k & 3;
+  return *reinterpret_cast<const bf16x8*>(sV + 4096 * db + vread[cc]);
+}
+
+constexpr int kPrefetch = 3;  // LDS fragments in flight ahead of the MFMA that consumes them
+constexpr int kDmaGap = 2;    // steps between two DMA issues of a stage
+
+// One pipeline stage (64 K/V columns).  H = stage parity (half of the mask tile), TAIL = the tile may contain
+// columns past the end of the sequence.
+//
+// The stage is written as 32 steps.  Step k issues the MFMA(s) of fragment k -- first the 16 of
+// O^T += V^T(s-1) P~^T(s-1), then the 16 of S^T(s+1) -- and one slice of the online softmax of stage s (vector
+// ALU), with scheduling fences between steps so that the compiler keeps this interleaving: the matrix cores and
+// the vector ALU of the SIMD then work at the same time inside one wave.  P~ of stage s is written over P~ of
+// stage s-1 word by word, each word after the last MFMA that reads it has been issued.
+template <int QB, int H, bool TAIL>
+__device__ __forceinline__ void stage(State<QB>& st, const Lane<QB>& ln, char* smem, int j_cur, int j_nxt,
+                                      int* flag_slot) {
+  f32x16(&cur)[QB][2] = H ? st.sB : st.sA;
+  f32x16(&nxt)[QB][2] = H ? st.sA : st.sB;
+
+  // ---- DMA: K of stage s+2 (next tile, same half) and V of this stage go into the buffers of parity H; the
+  // loads are issued one at a time between the steps below (kDmaGap steps apart) so that a full memory
+  // instruction queue does not hold up the MFMAs behind it ----
+  const uint32_t kbase = (uint32_t)(j_nxt * kTile + H * kSub) * ln.stride2;
+  const uint32_t vbase = (uint32_t)(j_cur * kTile + H * kSub) * 2u;
+  constexpr int kC = Geo<QB>::kChunks;
+
+  const char* sK = smem + kKOff + (H ^ 1) * kStageBytes;
+  const char* sV = smem + kVOff + (H ^ 1) * kStageBytes;
+  bf16x8 frag[kPrefetch];
+#pragma unroll
+  for (int k = 0; k < kPrefetch; ++k) frag[k] = load_frag(k, sK, sV, ln.kread, ln.vread);
+
+  float pm[QB][4], mx[QB], m_new[QB], mc[QB], alpha[QB], lsum[QB];
+  bool ok = true, grew = false;
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+
+#pragma unroll
+  for (int k = 0; k < 32; ++k) {
+    // ---- matrix cores ----
+    const bf16x8 a = frag[k % kPrefetch];
+    if (k >= 16) {
+      const int blk = (k - 16) >> 3, kk = k & 7;
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        if (kk == 0) {
+          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          nxt[qb][blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.qf[qb][kk], zero, 0, 0, 0);
+        } else {
+          nxt[qb][blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.qf[qb][kk], nxt[qb][blk], 0, 0, 0);
+        }
+      }
+    } else {
+      const int cc = k >> 2, db = k & 3;
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+        st.oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_operand(&st.pw[qb][4 * cc]), st.oacc[qb][db],
+                                                                  0, 0, 0);
+    }
+    if (k + kPrefetch < 32) frag[k % kPrefetch] = load_frag(k + kPrefetch, sK, sV, ln.kread, ln.vread);
+    if (k % kDmaGap == 0 && k / kDmaGap < 2 * kC) {
+      const int x = k / kDmaGap;
+      if (x < kC)
+        dma16(ln.vrsrc, ln.lds_wave + kVOff + H * kStageBytes + 1024 * x, ln.vdma[x] + vbase);
+      else
+        dma16(ln.krsrc, ln.lds_wave + kKOff + H * kStageBytes + 1024 * (x - kC), ln.kdma[x - kC] + kbase);
+    }
+
+    // ---- vector ALU: slice k of the online softmax of stage s (raw dot products; 1/sqrt(d) folded into c) ----
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      if (k < 4) {  // m_local: partial row maxima over 8 of this lane's 32 scores
+        const int blk = k >> 1, r0 = 8 * (k & 1);
+        if (TAIL) {
+          const int kv0 = j_cur * kTile + H * kSub;
+#pragma unroll
+          for (int r = r0; r < r0 + 8; ++r) {
+            const int col = kv0 + 32 * blk + 8 * (r >> 2) + 4 * ln.hi + (r & 3);
+            if (col >= ln.N) cur[qb][blk][r] = -INFINITY;
+          }
+        }
+        float v = cur[qb][blk][r0];
+#pragma unroll
+        for (int r = r0 + 1; r < r0 + 8; ++r) v = fmaxf(v, cur[qb][blk][r]);
+        pm[qb][k] = v;
+      } else if (k == 4) {
+        mx[qb] = other_half_max(fmaxf(fmaxf(pm[qb][0], pm[qb][1]), fmaxf(pm[qb][2], pm[qb][3])));
+      } else if (k == 5) {  // m_ij = max(m_{i,j-1}, m_local) and the rescale factor of the earlier stages
+        st.mloc_tile[qb] = H ? fmaxf(st.mloc_tile[qb], mx[qb]) : mx[qb];
+        m_new[qb] = fmaxf(st.m_run[qb], mx[qb]);
+        alpha[qb] = __builtin_amdgcn_exp2f((st.m_run[qb] - m_new[qb]) * ln.c);
+        grew = grew || (m_new[qb] > st.m_run[qb]);
+        st.m_run[qb] = m_new[qb];
+        mc[qb] = m_new[qb] * ln.c;
+        lsum[qb] = 0.f;
+      } else if (k < 22) {  // P~ = exp(S - m_ij) for two scores, packed to bf16
+        const int e = k - 6, blk = e >> 3, r = 2 * (e & 7);
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[qb][blk][r], ln.c, -mc[qb]));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[qb][blk][r + 1], ln.c, -mc[qb]));
+        uint32_t w = pack_bf16x2(p0, p1);
+        // the row sum adds the bf16-rounded weights, the same values the PV product uses
+        lsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, lsum[qb], false);
+        // an empty volatile asm pins this slice to step k: without it the compiler sinks all the exponentials
+        // behind the last MFMA, where nothing overlaps them
+        asm volatile("" : "+v"(w), "+v"(lsum[qb]));
+        st.pw[qb][e] = w;  // word e belongs to chunk e/4, whose last reader was the MFMA of step 4*(e/4)+3 < k
+      } else if (k == 22) {
+        st.l_run[qb] = st.l_run[qb] * alpha[qb] + lsum[qb];
+        if (H) {  // skip predicate of the whole 128-column tile, once its second half is in (eq. sparge_cond)
+          const float g = (st.mloc_tile[qb] - m_new[qb]) * ln.scale;  // this row; max over rows = ballot below
+          ok = ok && (!ln.qvalid[qb] || (g <= ln.thr));
+        }
+      }
+    }
+    if (H && k == 23) *flag_slot = __all(ok) ? 1 : 0;  // lane 0: the wave's slot; other lanes: a dummy word each
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  // O^T of the earlier stages is rescaled after this stage's PV MFMAs (rare once the running max has settled)
+  if (__any(grew)) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st.oacc[qb][db][r] *= alpha[qb];
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+}
+
+template <int QB>
+__global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kernel(const FwdParams p) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr int kWaves = Geo<QB>::kWaves, kThreads = Geo<QB>::kThreads, kChunks = Geo<QB>::kChunks;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int lq = lane & 31, hi = lane >> 5;
+  const int lq = lane & 31;
 
   // Consecutive workgroup ids land on different XCDs; give each XCD a contiguous range of rows so that the
   // workgroups sharing one L2 stream the K/V of the same head.
@@ -150,173 +389,150 @@ __global__ __launch_bounds__(kThreads, 2) void lite_attn_fwd_kernel(const FwdPar
   const int i = row % p.Tq;
   const int bh = row / p.Tq;
   const int64_t base = (int64_t)(bh / p.H) * p.stride_b + (int64_t)(bh % p.H) * p.stride_h;
-  const uint16_t* qb = p.q + base;
-  const uint16_t* kb = p.k + base;
-  const uint16_t* vb = p.v + base;
+  const uint16_t* qb_ptr = p.q + base;
   uint16_t* ob = p.out + base;
   const int N = p.N;
   const int cnt = (int)p.live_cnt[row];
-  const uint16_t* live = p.live_idx + (size_t)row * p.Tk;
+  // the Skip-List is read-only here: constant address space makes these wave-uniform reads scalar loads
+  typedef const __attribute__((address_space(4))) uint32_t* const_u32_ptr;
+  const_u32_ptr live32 = (const_u32_ptr)(p.live_idx + (size_t)row * p.live_stride);
   int* flags = reinterpret_cast<int*>(smem + kFlagsOff);
 
-  const int qrow = i * kTile + wave * 32 + lq;
-  const bool qvalid = qrow < N;
+  Lane<QB> ln;
+  ln.hi = lane >> 5;
+  ln.N = N;
+  ln.scale = p.scale;
+  ln.thr = p.thr;
+  ln.c = p.scale * 1.4426950408889634f;
+  ln.stride2 = (uint32_t)(p.stride_n * 2);
+  const uint32_t head_bytes = (uint32_t)(((int64_t)(N - 1) * p.stride_n + 128) * 2);
+  ln.krsrc = make_rsrc(p.k + base, head_bytes);
+  const uint32_t vt_row_bytes = (uint32_t)p.Tk * kTile * 2;  // one feature row of V^T: n_pad bf16
+  ln.vrsrc = make_rsrc(p.vt + (size_t)bh * 128 * ((size_t)p.Tk * kTile), 128u * vt_row_bytes);
+  ln.lds_wave = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(LA_LDS char*)smem + 1024 * kChunks * wave);
+#pragma unroll
+  for (int x = 0; x < kChunks; ++x) {
+    const int r = 4 * (kChunks * wave + x) + (lane >> 4);  // row inside the stage that this lane's piece belongs to
+    const int pc = lane & 15;                              // physical 16-byte chunk inside the 256-byte LDS row
+    ln.kdma[x] = (uint32_t)r * ln.stride2 + 16 * (pc ^ (r & 15));
+    // V^T stage: 128 feature rows x 128 bytes; this lane's piece is row rv, physical 16-byte slot pv
+    const int rv = 8 * (kChunks * wave + x) + (lane >> 3), pv = lane & 7;
+    ln.vdma[x] = (uint32_t)rv * vt_row_bytes + 16 * (pv ^ ((rv >> 1) & 7));
+  }
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) ln.kread[kk] = lq * 256 + ((32 * kk) ^ (16 * (ln.hi ^ (lq & 15))));
+#pragma unroll
+  for (int cc = 0; cc < 4; ++cc) ln.vread[cc] = lq * 128 + ((32 * cc + 16 * ln.hi) ^ (16 * ((lq >> 1) & 7)));
   const bool q_pinned = p.protect_len > 0 && i * kTile < p.protect_start + p.protect_len &&
                         p.protect_start < min(N, (i + 1) * kTile);
 
-  // Q^T fragments: B operand of S^T = K Q^T, kept for the whole row.
-  bf16x8 qf[8];
+  State<QB> st;
 #pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    uint4 raw = {0u, 0u, 0u, 0u};
-    if (qvalid) raw = ld16(qb + (int64_t)qrow * p.stride_n + 16 * kk + 8 * hi);
-    qf[kk] = *reinterpret_cast<bf16x8*>(&raw);
-  }
-
-  f32x16 oacc[4];
+  for (int qb = 0; qb < QB; ++qb) {
+    const int qrow = i * kTile + 32 * (QB * wave + qb) + lq;
+    ln.qvalid[qb] = qrow < N;
+    // Q^T fragments: B operand of S^T = K Q^T, kept for the whole row.
 #pragma unroll
-  for (int db = 0; db < 4; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-  float m_run = -INFINITY;  // running row max of the raw dot products (m_{i,j-1} * sqrt(d))
-  float l_run = 0.f;        // this lane's half of the row sum
-  float mloc_tile = -INFINITY;
-  const float c = p.scale * 1.4426950408889634f;  // exp(x*scale) = exp2(x*c)
-  unsigned newly = 0;
-
-  const int nsub = 2 * cnt;
-  StageRegs regs;
-  if (nsub > 0) {
-    load_stage(regs, kb, vb, p.stride_n, (int)live[0] * kTile, N, tid);
-    store_stage(regs, smem, tid);
-  }
-  __syncthreads();
-
-  for (int s = 0; s < nsub; ++s) {
-    const int j = (int)live[s >> 1];
-    const int half = s & 1;
-    const int kv0 = j * kTile + half * kSub;
-    char* stage = smem + (s & 1) * kStage;
-    const bool more = (s + 1) < nsub;
-    if (more) {
-      const int jn = (int)live[(s + 1) >> 1];
-      load_stage(regs, kb, vb, p.stride_n, jn * kTile + ((s + 1) & 1) * kSub, N, tid);
+    for (int kk = 0; kk < 8; ++kk) {
+      uint4 raw = {0u, 0u, 0u, 0u};
+      if (ln.qvalid[qb])
+        raw = *reinterpret_cast<const uint4*>(qb_ptr + (int64_t)qrow * p.stride_n + 16 * kk + 8 * ln.hi);
+      st.qf[qb][kk] = *reinterpret_cast<bf16x8*>(&raw);
     }
-
-    // ---- S^T = K Q^T for 64 K/V columns (raw dot products; the 1/sqrt(d) is folded into c) ----
-    f32x16 sacc[2];
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[blk][r] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(stage + (32 * blk + lq) * kKRow + 32 * kk + 16 * hi);
-        sacc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], sacc[blk], 0, 0, 0);
-      }
-    }
-    // columns past the end of the sequence do not exist: exclude them from max and sum
-    if (kv0 + kSub > N) {
-#pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int col = kv0 + 32 * blk + 8 * (r >> 2) + 4 * hi + (r & 3);
-          if (col >= N) sacc[blk][r] = -INFINITY;
-        }
-    }
-
-    // ---- online softmax: m_local, m_ij, P~ ----
-    float mx = sacc[0][0];
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[blk][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    mloc_tile = half ? fmaxf(mloc_tile, mx) : mx;
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-    const float mc = m_new * c;
-    float lsum = 0.f;
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pexp = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[blk][r], c, -mc));
-        sacc[blk][r] = pexp;
-        lsum += pexp;
-      }
-    l_run = l_run * alpha + lsum;
-    if (__any(m_new > m_run)) {
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-    }
-    m_run = m_new;
-
-    // ---- skip predicate of the whole 128-column tile, once its second half is in ----
-    if (half) {
-      const float g = (mloc_tile - m_run) * p.scale;  // max over rows is the ballot below
-      const bool ok = !qvalid || (g <= p.thr);
-      const bool wave_all = __all(ok);
-      if (lane == 0) flags[((s >> 1) & 1) * 4 + wave] = wave_all ? 1 : 0;
-    }
-
-    // ---- P~ in accumulator layout is the B operand of O^T += V^T P~^T ----
-    bf16x8 pf[4];
-#pragma unroll
-    for (int cc = 0; cc < 4; ++cc) {
-      const int blk = cc >> 1, r0 = 8 * (cc & 1);
-      uint4 raw;
-      raw.x = pack_bf16x2(sacc[blk][r0 + 0], sacc[blk][r0 + 1]);
-      raw.y = pack_bf16x2(sacc[blk][r0 + 2], sacc[blk][r0 + 3]);
-      raw.z = pack_bf16x2(sacc[blk][r0 + 4], sacc[blk][r0 + 5]);
-      raw.w = pack_bf16x2(sacc[blk][r0 + 6], sacc[blk][r0 + 7]);
-      pf[cc] = *reinterpret_cast<bf16x8*>(&raw);
-    }
-    const char* sVt = stage + kKBytes;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int cc = 0; cc < 4; ++cc) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sVt + (32 * db + lq) * kVtRow + 32 * cc + 16 * hi);
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[cc], oacc[db], 0, 0, 0);
-      }
+      for (int r = 0; r < 16; ++r) st.oacc[qb][db][r] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) st.pw[qb][e] = 0u;
+    st.m_run[qb] = -INFINITY;  // running row max of the raw dot products (m_{i,j-1} * sqrt(d))
+    st.l_run[qb] = 0.f;        // this lane's half of the row sum
+    st.mloc_tile[qb] = -INFINITY;
+  }
+  unsigned newly = 0;
 
-    if (more) store_stage(regs, smem + ((s + 1) & 1) * kStage, tid);
+  // lane 0 writes the wave's predicate flag, every other lane a private dummy word (keeps the stage branch-free)
+  int* flag_slot0 = lane == 0 ? flags + wave : flags + 8 + lane;
+  int* flag_slot1 = lane == 0 ? flags + 4 + wave : flags + 8 + lane;
+
+  if (cnt > 0) {
+    auto tile_at = [&](int t) -> int {
+      const uint32_t w = live32[t >> 1];
+      return (int)((t & 1) ? (w >> 16) : (w & 0xffffu));
+    };
+    int j_cur = tile_at(0);
+    int j_nxt = tile_at(min(1, cnt - 1));
+    // the last live tile needs column masking if it is the ragged last tile of the sequence
+    const bool tail = (N & (kTile - 1)) != 0 && tile_at(cnt - 1) == p.Tk - 1;
+    const int n_main = tail ? cnt - 1 : cnt;
+
+    // prologue: the odd V^T buffer is read (times P~ = 0) before it is first filled: make it finite; K of
+    // stages 0 and 1; then S^T(0)
+    for (int x = tid; x < kStageBytes / 16; x += kThreads)
+      *reinterpret_cast<uint4*>(smem + kVOff + kStageBytes + 16 * x) = uint4{0u, 0u, 0u, 0u};
+    dma_stage<QB>(ln.krsrc, ln.kdma, (uint32_t)(j_cur * kTile) * ln.stride2, ln.lds_wave + kKOff);
+    dma_stage<QB>(ln.krsrc, ln.kdma, (uint32_t)(j_cur * kTile + kSub) * ln.stride2,
+                  ln.lds_wave + kKOff + kStageBytes);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    mma_qk<QB>(st.sA, st.qf, smem + kKOff, ln.kread);
     __syncthreads();
 
-    // ---- the four per-wave results of the finished tile meet here; one lane updates the mask ----
-    if (half && tid == 0) {
-      const int* f = flags + ((s >> 1) & 1) * 4;
-      const bool k_pinned = p.protect_len > 0 && j * kTile < p.protect_start + p.protect_len &&
-                            p.protect_start < min(N, (j + 1) * kTile);
-      if ((f[0] & f[1] & f[2] & f[3]) && !q_pinned && !k_pinned) {
-        atomicOr(reinterpret_cast<unsigned long long*>(p.bits + (size_t)row * p.W + (j >> 6)), 1ull << (j & 63));
-        ++newly;
+    auto finish_tile = [&](int t, int j) {
+      // the per-wave results of the finished tile meet here; one lane updates the mask
+      if (tid == 0) {
+        const int* f = flags + (t & 1) * 4;
+        int all = 1;
+        for (int w = 0; w < kWaves; ++w) all &= f[w];
+        const bool k_pinned = p.protect_len > 0 && j * kTile < p.protect_start + p.protect_len &&
+                              p.protect_start < min(N, (j + 1) * kTile);
+        if (all && !q_pinned && !k_pinned) {
+          atomicOr(reinterpret_cast<unsigned long long*>(p.bits + (size_t)row * p.W + (j >> 6)), 1ull << (j & 63));
+          ++newly;
+        }
       }
+    };
+    for (int t = 0; t < n_main; ++t) {
+      const int j_nn = tile_at(min(t + 2, cnt - 1));  // needed one tile from now: its latency is hidden
+      int* fs = (t & 1) ? flag_slot1 : flag_slot0;
+      stage<QB, 0, false>(st, ln, smem, j_cur, j_nxt, fs);
+      stage<QB, 1, false>(st, ln, smem, j_cur, j_nxt, fs);
+      finish_tile(t, j_cur);
+      j_cur = j_nxt;
+      j_nxt = j_nn;
     }
+    if (tail) {
+      int* fs = (n_main & 1) ? flag_slot1 : flag_slot0;
+      stage<QB, 0, true>(st, ln, smem, j_cur, j_cur, fs);
+      stage<QB, 1, true>(st, ln, smem, j_cur, j_cur, fs);
+      finish_tile(n_main, j_cur);
+    }
+    // drain: O^T += V^T P~^T of the last stage (odd parity buffer)
+    mma_pv<QB>(st.oacc, st.pw, smem + kVOff + kStageBytes, ln.vread);
+    __syncthreads();
   }
   if (tid == 0 && newly) atomicAdd(p.stat_newly, (unsigned long long)newly);
 
   // ---- epilogue: O = acc / l, transposed through LDS so that global stores are 16 B and row-contiguous ----
-  const float l = l_run + __shfl_xor(l_run, 32);
-  const float inv = (l > 0.f) ? 1.f / l : 0.f;
   char* sO = smem;
 #pragma unroll
-  for (int db = 0; db < 4; ++db)
+  for (int qb = 0; qb < QB; ++qb) {
+    const float l = other_half_sum(st.l_run[qb]);
+    const float inv = (l > 0.f) ? 1.f / l : 0.f;
 #pragma unroll
-    for (int rg = 0; rg < 4; ++rg) {
-      uint2 w;
-      w.x = pack_bf16x2(oacc[db][4 * rg + 0] * inv, oacc[db][4 * rg + 1] * inv);
-      w.y = pack_bf16x2(oacc[db][4 * rg + 2] * inv, oacc[db][4 * rg + 3] * inv);
-      *reinterpret_cast<uint2*>(sO + (32 * wave + lq) * kORow + 2 * (32 * db + 8 * rg + 4 * hi)) = w;
-    }
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        uint2 w;
+        w.x = pack_bf16x2(st.oacc[qb][db][4 * rg + 0] * inv, st.oacc[qb][db][4 * rg + 1] * inv);
+        w.y = pack_bf16x2(st.oacc[qb][db][4 * rg + 2] * inv, st.oacc[qb][db][4 * rg + 3] * inv);
+        *reinterpret_cast<uint2*>(sO + (32 * (QB * wave + qb) + lq) * kORow + 2 * (32 * db + 8 * rg + 4 * ln.hi)) = w;
+      }
+  }
   __syncthreads();
 #pragma unroll
-  for (int t = 0; t < 8; ++t) {
-    const int r = (tid >> 4) + 16 * t;
+  for (int t = 0; t < 2048 / kThreads; ++t) {
+    const int r = (tid >> 4) + (kThreads / 16) * t;
     const int grow = i * kTile + r;
     if (grow < N)
       *reinterpret_cast<uint4*>(ob + (int64_t)grow * p.stride_n + 8 * (tid & 15)) =
@@ -324,7 +540,7 @@ __global__ __launch_bounds__(kThreads, 2) void lite_attn_fwd_kernel(const FwdPar
   }
 }
 
-int fwd_lds_bytes() { return kFlagsOff + 32; }
+int fwd_lds_bytes() { return kLdsBytes; }
 
 hipError_t launch_clear(uint64_t* bits, size_t words, unsigned long long* stats, size_t nstats, hipStream_t st) {
   size_t n = words > nstats ? words : nstats;
@@ -335,21 +551,30 @@ hipError_t launch_clear(uint64_t* bits, size_t words, unsigned long long* stats,
   return hipGetLastError();
 }
 
-hipError_t launch_compact(const uint64_t* bits, int rows, int Tk, int W, uint16_t* live_idx, uint32_t* live_cnt,
-                          unsigned long long* stat_skipped_in, hipStream_t st) {
-  hipLaunchKernelGGL(compact_skiplist, dim3((rows + 3) / 4), dim3(256), 0, st, bits, rows, Tk, W, live_idx, live_cnt,
-                     stat_skipped_in);
+hipError_t launch_compact(const uint64_t* bits, int rows, int Tk, int W, int live_stride, uint16_t* live_idx,
+                          uint32_t* live_cnt, unsigned long long* stat_skipped_in, hipStream_t st) {
+  hipLaunchKernelGGL(compact_skiplist, dim3((rows + 3) / 4), dim3(256), 0, st, bits, rows, Tk, W, live_stride,
+                     live_idx, live_cnt, stat_skipped_in);
   return hipGetLastError();
 }
 
+hipError_t launch_transpose_v(const uint16_t* v, uint16_t* vt, int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                              int BH, int H, int N, int Tk, hipStream_t st) {
+  hipLaunchKernelGGL(transpose_v_kernel, dim3((unsigned)(BH * Tk)), dim3(256), 0, st, v, vt, stride_b, stride_h,
+                     stride_n, H, N, Tk);
+  return hipGetLastError();
+}
+
+constexpr int kQB = 1;  // 32 Q rows per wave, 4 waves per workgroup, 2 workgroups per CU
+
 hipError_t prepare_fwd() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(lite_attn_fwd_kernel),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(lite_attn_fwd_kernel<kQB>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, fwd_lds_bytes());
 }
 
 hipError_t launch_fwd(const FwdParams& p, hipStream_t st) {
   const int grid = 8 * p.rows_per_xcd;
-  hipLaunchKernelGGL(lite_attn_fwd_kernel, dim3(grid), dim3(kThreads), fwd_lds_bytes(), st, p);
+  hipLaunchKernelGGL(lite_attn_fwd_kernel<kQB>, dim3(grid), dim3(Geo<kQB>::kThreads), fwd_lds_bytes(), st, p);
   return hipGetLastError();
 }
 
