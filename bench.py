@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the LiteAttention hot path on one MI355X.
 
-A "step" is one denoising timestep of one attention layer: one lite_attn_fwd call (Skip-List compaction +
+A "step" is one denoising timestep of one attention layer: one lite_attn_fwd call (Skip-List compaction, V^T pre-pass,
 fused skip-aware attention) over one set of synthetic Q, K, V already resident in HBM.  The timed region is
 the first K steps of a fresh trajectory (step 0 starts from an empty Skip-Mask, i.e. the dense path; later
 steps skip what earlier steps marked).  Prints ONE JSON line.
@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--workload", default="wan14b")
     ap.add_argument("--threshold", type=float, default=None)
     ap.add_argument("--cpu-rows", type=int, default=None, help="Q-tile rows the oracle baseline runs (0 = skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (heads shard across GPUs with no collective; see DESIGN.md); "
@@ -86,12 +88,24 @@ def main():
             q, k, v = data[t % K]
             la.lite_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), handle, thr, t)
 
+    if args.copy_calibration:       # a copy kernel of known size: reads 1 GiB, writes 1 GiB
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     run(W)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run(K)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+
+    # practical matrix-core ceiling on this workload's own bit patterns (register-resident MFMA loop, ~5 ms)
+    # (operands: this workload's V, i.e. N(0,1) values; and K rows from the middle of the sequence)
+    stream = torch.cuda.current_stream().cuda_stream
+    mfma_peak_measured = la.lite_attn_mfma_peak(stream, data[0][2].data_ptr())
+    mfma_peak_k = la.lite_attn_mfma_peak(stream, data[0][1][0, 0, N // 2].data_ptr())
 
     per_step = []
     live_flop = 0.0
@@ -104,7 +118,7 @@ def main():
         fwd_ms_total += fms
         per_step.append({"step": t, "skip_ratio": round(st.tiles_skipped_in / st.tiles_total, 4),
                          "newly_marked": round(st.tiles_newly_marked / st.tiles_total, 4),
-                         "compact_ms": round(cms, 4), "attn_ms": round(fms, 3),
+                         "prep_ms": round(cms, 4), "attn_ms": round(fms, 3),
                          "attn_tflops_live": round(live * TILE_FLOP / fms / 1e9, 1)})
     la.lite_attn_free_mask(handle)
 
@@ -121,11 +135,15 @@ def main():
             "threshold": thr, "mask_tile": "128x128",
             "mean_skip_ratio": round(sum(s["skip_ratio"] for s in per_step) / K, 4)},
         "dense_step": {"ms": per_step[0]["attn_ms"], "tflops": per_step[0]["attn_tflops_live"],
-                       "frac_of_bf16_peak": round(per_step[0]["attn_tflops_live"] / PEAK_BF16_TFLOPS, 4)},
+                       "frac_of_bf16_peak": round(per_step[0]["attn_tflops_live"] / PEAK_BF16_TFLOPS, 4),
+                       "frac_of_measured_mfma_only": round(per_step[0]["attn_tflops_live"] / mfma_peak_measured, 4)},
         "per_step": per_step,
         "roofline": {"bound": "mfma", "kernel": "lite_attn_fwd_kernel", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": None,
+                     "measured_mfma_only_tflops": round(mfma_peak_measured, 1),
+                     "measured_mfma_only_tflops_on_k": round(mfma_peak_k, 1),
+                     "frac_of_measured_mfma_only": round(achieved / mfma_peak_measured, 4),
                      "note": "achieved = 8.39 MFLOP x live tiles of the K timed launches / their summed HIP-event "
                              "durations"},
     }

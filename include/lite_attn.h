@@ -55,7 +55,8 @@ typedef struct {
 } lite_attn_desc_t;
 
 /* Opaque handle: owns the device Skip-Mask ([B,H,Tq,ceil(Tk/64)] uint64, bit j%64 of word j/64 set = tile (i,j)
-   skipped), the Skip-List buffers and the statistics.  Tq = ceil(N/tile_q), Tk = ceil(N/tile_k). */
+   skipped), the Skip-List buffers, a scratch copy of V^T (same size as V) and the statistics.
+   Tq = ceil(N/tile_q), Tk = ceil(N/tile_k). */
 typedef struct lite_attn_mask lite_attn_mask_t;
 
 typedef struct {
@@ -90,12 +91,20 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
    Synchronises the handle's stream. */
 int lite_attn_skip_stats(lite_attn_mask_t* mask, int step, lite_attn_stats_t* host_out);
 
-/* Per-kernel timing for benchmarks.  enable != 0 makes every later lite_attn_fwd record HIP events on the handle's
-   stream around its two kernels (events are created on the first enabled call; a few microseconds per call).
-   lite_attn_kernel_times returns the durations of a completed step in milliseconds; it synchronises the stream
-   and fails with LITE_ATTN_ESTEP if that step was not run with profiling enabled. */
+/* Per-phase timing for benchmarks.  enable != 0 makes every later lite_attn_fwd record HIP events on the handle's
+   stream around its two phases (events are created on the first enabled call; a few microseconds per call).
+   lite_attn_kernel_times returns the durations of a completed step in milliseconds -- host_prep_ms: Skip-List
+   compaction plus the V transposition pre-pass; host_fwd_ms: the fused attention kernel -- it synchronises the
+   stream and fails with LITE_ATTN_ESTEP if that step was not run with profiling enabled. */
 int lite_attn_profile(lite_attn_mask_t* mask, int enable);
-int lite_attn_kernel_times(lite_attn_mask_t* mask, int step, float* host_compact_ms, float* host_fwd_ms);
+int lite_attn_kernel_times(lite_attn_mask_t* mask, int step, float* host_prep_ms, float* host_fwd_ms);
+
+/* Benchmark diagnostic: times a register-resident loop of v_mfma_f32_32x32x16_bf16 (no memory traffic, 2 waves per
+   SIMD on every CU) whose A/B operands are taken from `dev_operands` (device pointer, at least 64 KiB, read as bf16).
+   The sustained matrix-core clock depends on the operands' bit patterns (power), so this is the practical ceiling
+   of the fused kernel on the same kind of data.  Runs `iters` x 32 MFMAs per wave on `hip_stream`, synchronises,
+   and returns the elapsed milliseconds and the flop count. */
+int lite_attn_mfma_peak(void* hip_stream, const void* dev_operands, int iters, float* host_ms, double* host_flops);
 
 /* Number of uint64 words of the whole mask: B*H*Tq*ceil(Tk/64). */
 size_t lite_attn_mask_words(const lite_attn_mask_t* mask);

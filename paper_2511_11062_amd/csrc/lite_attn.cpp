@@ -17,12 +17,13 @@ struct lite_attn_mask {
   uint64_t* d_bits;
   uint16_t* d_live_idx;
   uint32_t* d_live_cnt;
+  uint32_t* d_order;  // [B*H][Tq] rows of each head ranked by Skip-List length
   uint16_t* d_vt;  // V^T scratch of the current call: [B*H][128][128*Tk] bf16
   unsigned long long* d_stats;  // [max_steps][2]: skipped on entry, newly marked
   hipStream_t stream;
   int next_step;
   bool profile;
-  hipEvent_t* events;  // [max_steps][3] once profiling was enabled: before compaction, between, after attention
+  hipEvent_t* events;  // [max_steps][3] once profiling was enabled: before the pre-passes, between, after attention
   bool* timed;         // [max_steps]
 };
 
@@ -85,10 +86,11 @@ int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out) {
   m->profile = false;
   m->events = nullptr;
   m->timed = nullptr;
-  m->d_bits = nullptr; m->d_live_idx = nullptr; m->d_live_cnt = nullptr; m->d_stats = nullptr; m->d_vt = nullptr;
+  m->d_bits = nullptr; m->d_live_idx = nullptr; m->d_live_cnt = nullptr; m->d_stats = nullptr; m->d_vt = nullptr; m->d_order = nullptr;
   hipError_t e = hipMalloc(&m->d_bits, sizeof(uint64_t) * (size_t)m->rows * m->W);
   if (e == hipSuccess) e = hipMalloc(&m->d_live_idx, sizeof(uint16_t) * (size_t)m->rows * m->live_stride);
   if (e == hipSuccess) e = hipMalloc(&m->d_live_cnt, sizeof(uint32_t) * (size_t)m->rows);
+  if (e == hipSuccess) e = hipMalloc(&m->d_order, sizeof(uint32_t) * (size_t)m->rows);
   if (e == hipSuccess)
     e = hipMalloc(&m->d_vt, sizeof(uint16_t) * (size_t)desc->batch * desc->heads * 128 * ((size_t)m->Tk * 128));
   if (e == hipSuccess) e = hipMalloc(&m->d_stats, sizeof(unsigned long long) * 2 * (size_t)desc->max_steps);
@@ -127,6 +129,7 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
   if (ev) LA_HIP(hipEventRecord(ev[0], m->stream));
   LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->live_stride, m->d_live_idx, m->d_live_cnt, st,
                             m->stream));
+  LA_HIP(la::launch_order_rows(m->d_live_cnt, d.batch * d.heads, m->Tq, m->Tk, m->d_order, m->stream));
   LA_HIP(la::launch_transpose_v(static_cast<const uint16_t*>(v), m->d_vt, d.stride_b, d.stride_h, d.stride_n,
                                 d.batch * d.heads, d.heads, d.seqlen, m->Tk, m->stream));
   la::FwdParams p;
@@ -142,7 +145,7 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
   p.scale = 1.0f / std::sqrt((float)d.head_dim);
   p.protect_start = d.protect_start; p.protect_len = d.protect_len;
   p.rows_total = (int)m->rows;
-  p.rows_per_xcd = (int)((m->rows + 7) / 8);
+  p.order = m->d_order;
   if (ev) LA_HIP(hipEventRecord(ev[1], m->stream));
   LA_HIP(la::launch_fwd(p, m->stream));
   if (ev) LA_HIP(hipEventRecord(ev[2], m->stream));
@@ -191,13 +194,39 @@ int lite_attn_profile(lite_attn_mask_t* m, int enable) {
   return LITE_ATTN_OK;
 }
 
-int lite_attn_kernel_times(lite_attn_mask_t* m, int step, float* host_compact_ms, float* host_fwd_ms) {
-  if (!m || !host_compact_ms || !host_fwd_ms) return LITE_ATTN_EINVAL;
+int lite_attn_kernel_times(lite_attn_mask_t* m, int step, float* host_prep_ms, float* host_fwd_ms) {
+  if (!m || !host_prep_ms || !host_fwd_ms) return LITE_ATTN_EINVAL;
   if (step < 0 || step >= m->desc.max_steps || !m->events || !m->timed[step]) return LITE_ATTN_ESTEP;
   hipEvent_t* ev = m->events + 3 * (size_t)step;
   LA_HIP(hipEventSynchronize(ev[2]));
-  LA_HIP(hipEventElapsedTime(host_compact_ms, ev[0], ev[1]));
+  LA_HIP(hipEventElapsedTime(host_prep_ms, ev[0], ev[1]));
   LA_HIP(hipEventElapsedTime(host_fwd_ms, ev[1], ev[2]));
+  return LITE_ATTN_OK;
+}
+
+int lite_attn_mfma_peak(void* hip_stream, const void* dev_operands, int iters, float* host_ms, double* host_flops) {
+  if (!dev_operands || !host_ms || !host_flops || iters < 1 || iters > (1 << 20)) return LITE_ATTN_EINVAL;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  int dev = 0, cus = 0;
+  LA_HIP(hipGetDevice(&dev));
+  LA_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  const int blocks = 2 * cus;  // 2 workgroups of 4 waves per CU: 2 waves per SIMD
+  float* sink = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipError_t e = hipMalloc(&sink, sizeof(float));
+  if (e == hipSuccess) e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  if (e == hipSuccess) e = la::launch_mfma_peak(dev_operands, sink, 64, blocks, st);  // warm-up
+  if (e == hipSuccess) e = hipEventRecord(e0, st);
+  if (e == hipSuccess) e = la::launch_mfma_peak(dev_operands, sink, iters, blocks, st);
+  if (e == hipSuccess) e = hipEventRecord(e1, st);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  if (e == hipSuccess) e = hipEventElapsedTime(host_ms, e0, e1);
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (sink) (void)hipFree(sink);
+  if (e != hipSuccess) return hip_fail(e);
+  *host_flops = (double)blocks * 4.0 * (double)iters * 32.0 * (2.0 * 32 * 32 * 16);
   return LITE_ATTN_OK;
 }
 
@@ -239,6 +268,7 @@ void lite_attn_free_mask(lite_attn_mask_t* m) {
   if (m->d_live_cnt) (void)hipFree(m->d_live_cnt);
   if (m->d_stats) (void)hipFree(m->d_stats);
   if (m->d_vt) (void)hipFree(m->d_vt);
+  if (m->d_order) (void)hipFree(m->d_order);
   if (m->events) {
     for (size_t x = 0; x < 3 * (size_t)m->desc.max_steps; ++x) (void)hipEventDestroy(m->events[x]);
     delete[] m->events;

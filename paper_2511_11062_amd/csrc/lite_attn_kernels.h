@@ -21,7 +21,8 @@ struct FwdParams {
   float thr;                             // signed threshold, natural-log units of S
   float scale;                           // 1/sqrt(d)
   int protect_start, protect_len;
-  int rows_total, rows_per_xcd;
+  int rows_total;                        // B*H*Tq
+  const uint32_t* order;                 // [B*H][Tq]: Q tiles of each head ranked by Skip-List length, longest first
 };
 
 int fwd_lds_bytes();
@@ -31,6 +32,8 @@ hipError_t launch_compact(const uint64_t* bits, int rows, int Tk, int W, int liv
                           uint32_t* live_cnt, unsigned long long* stat_skipped_in, hipStream_t st);
 hipError_t launch_transpose_v(const uint16_t* v, uint16_t* vt, int64_t stride_b, int64_t stride_h, int64_t stride_n,
                               int BH, int H, int N, int Tk, hipStream_t st);
+hipError_t launch_mfma_peak(const void* data, float* sink, int iters, int blocks, hipStream_t st);
+hipError_t launch_order_rows(const uint32_t* live_cnt, int BH, int Tq, int Tk, uint32_t* order, hipStream_t st);
 hipError_t launch_fwd(const FwdParams& p, hipStream_t st);
 
 }  // namespace la

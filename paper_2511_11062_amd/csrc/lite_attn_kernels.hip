@@ -100,6 +100,34 @@ __device__ __forceinline__ float other_half_sum(float x) {
   return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
 }
 
+// Row schedule.  For every head, ranks its Q-tile rows by the length of their Skip-List, longest first (counting
+// sort: one workgroup per head, histogram in LDS).  The fused kernel walks each head's rows in this order, so that
+// the rows left over at the end of the launch are the shortest ones, and spreads rank-chunks of every head over
+// all XCDs, so that every XCD gets the same mix of long and short rows whatever the sparsity of individual heads.
+__global__ __launch_bounds__(256) void order_rows_kernel(const uint32_t* __restrict__ live_cnt, int Tq, int Tk,
+                                                          uint32_t* __restrict__ order) {
+  extern __shared__ uint32_t hist[];  // Tk + 1 bins; bin b counts rows with Tk - b live tiles
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  const uint32_t* cnt = live_cnt + (size_t)bh * Tq;
+  for (int b = tid; b <= Tk; b += 256) hist[b] = 0;
+  __syncthreads();
+  for (int i = tid; i < Tq; i += 256) atomicAdd(&hist[Tk - min((int)cnt[i], Tk)], 1u);
+  __syncthreads();
+  if (tid == 0) {  // exclusive prefix sum over at most 16384 bins
+    uint32_t run = 0;
+    for (int b = 0; b <= Tk; ++b) {
+      const uint32_t c = hist[b];
+      hist[b] = run;
+      run += c;
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < Tq; i += 256) {
+    const uint32_t pos = atomicAdd(&hist[Tk - min((int)cnt[i], Tk)], 1u);
+    order[(size_t)bh * Tq + pos] = (uint32_t)i;
+  }
+}
+
 // V -> V^T pre-pass.  The PV product contracts over the K/V index, so the matrix cores want, per lane, 8 V values
 // of ONE feature d at 8 K/V positions: a 16-byte read from a [d][kv] layout, but a strided gather from V's [kv][d].
 // (gfx950's transposing LDS read, ds_read_b64_tr_b16, delivers only 8 bytes per lane and measured at a third of the
@@ -246,6 +274,7 @@ __device__ __forceinline__ bf16x8 load_frag(int k, const char* sK, const char* s
   return *reinterpret_cast<const bf16x8*>(sV + 4096 * db + vread[cc]);
 }
 
+constexpr int kChunkRows = 64;  // rows of one head that an XCD runs side by side (2 workgroups x 32 CUs)
 constexpr int kPrefetch = 3;  // LDS fragments in flight ahead of the MFMA that consumes them
 constexpr int kDmaGap = 2;    // steps between two DMA issues of a stage
 
@@ -380,12 +409,31 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lq = lane & 31;
 
-  // Consecutive workgroup ids land on different XCDs; give each XCD a contiguous range of rows so that the
-  // workgroups sharing one L2 stream the K/V of the same head.
+  // Consecutive workgroup ids land on different XCDs (id % 8).  The rows of every head, ranked longest first by
+  // order_rows_kernel, are cut into chunks of kChunkRows ("rank c" = rows ranked [c*kChunkRows, (c+1)*kChunkRows)).
+  // The chunks are numbered rank-major, u = c * BH + (h + c) % BH, and dealt to the XCDs round-robin (u % 8); an XCD
+  // walks its chunks in that order.  So the workgroups sharing one L2 stream the K/V of the same head, a head's
+  // chunks rotate over the XCDs (every XCD gets the same share of every rank, whatever the sparsity of individual
+  // heads), and the launch ends with the shortest rows.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  if (slot >= p.rows_per_xcd) return;
-  const int row = xcd * p.rows_per_xcd + slot;
-  if (row >= p.rows_total) return;
+  const int BH = p.rows_total / p.Tq;
+  const int ranks = (p.Tq + kChunkRows - 1) / kChunkRows;
+  const int len_last = p.Tq - (ranks - 1) * kChunkRows;
+  const int full_units = (ranks - 1) * BH;                    // chunks u < full_units have kChunkRows rows
+  const int k_full = full_units > xcd ? (full_units - xcd + 7) >> 3 : 0;  // how many of them this XCD owns
+  int k, r;
+  if (slot < kChunkRows * k_full) {
+    k = slot / kChunkRows;
+    r = slot % kChunkRows;
+  } else {
+    k = k_full + (slot - kChunkRows * k_full) / len_last;
+    r = (slot - kChunkRows * k_full) % len_last;
+  }
+  const int u = xcd + 8 * k;
+  if (u >= ranks * BH) return;
+  const int c = u / BH;
+  const int bh_ = ((u % BH) - (c % BH) + BH) % BH;
+  const int row = bh_ * p.Tq + (int)p.order[(size_t)bh_ * p.Tq + c * kChunkRows + r];
   const int i = row % p.Tq;
   const int bh = row / p.Tq;
   const int64_t base = (int64_t)(bh / p.H) * p.stride_b + (int64_t)(bh % p.H) * p.stride_h;
@@ -540,6 +588,40 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
   }
 }
 
+// Register-resident MFMA loop for the benchmark's "measured matrix-core ceiling": 8 A and 8 B fragments per lane
+// read once from `data`, then iters x 32 MFMAs on four independent accumulators.
+__global__ __launch_bounds__(256, 2) void mfma_peak_kernel(const uint4* __restrict__ data, float* __restrict__ sink,
+                                                            int iters) {
+  bf16x8 a[8], b[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const uint4 x = data[(threadIdx.x + 256 * i) & 4095], y = data[(threadIdx.x + 256 * i + 2048) & 4095];
+    a[i] = __builtin_bit_cast(bf16x8, x);
+    b[i] = __builtin_bit_cast(bf16x8, y);
+  }
+  f32x16 acc[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 32; ++u)
+      acc[u & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u & 7], b[(u >> 2) & 7], acc[u & 3], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[n][r];
+  if (s == 12345.678f) sink[0] = s;  // keeps the loop alive without a store in the common case
+}
+
+hipError_t launch_mfma_peak(const void* data, float* sink, int iters, int blocks, hipStream_t st) {
+  hipLaunchKernelGGL(mfma_peak_kernel, dim3(blocks), dim3(256), 0, st, static_cast<const uint4*>(data), sink, iters);
+  return hipGetLastError();
+}
+
 int fwd_lds_bytes() { return kLdsBytes; }
 
 hipError_t launch_clear(uint64_t* bits, size_t words, unsigned long long* stats, size_t nstats, hipStream_t st) {
@@ -572,9 +654,18 @@ hipError_t prepare_fwd() {
                              hipFuncAttributeMaxDynamicSharedMemorySize, fwd_lds_bytes());
 }
 
+hipError_t launch_order_rows(const uint32_t* live_cnt, int BH, int Tq, int Tk, uint32_t* order, hipStream_t st) {
+  hipLaunchKernelGGL(order_rows_kernel, dim3(BH), dim3(256), sizeof(uint32_t) * (size_t)(Tk + 1), st, live_cnt, Tq, Tk,
+                     order);
+  return hipGetLastError();
+}
+
 hipError_t launch_fwd(const FwdParams& p, hipStream_t st) {
-  const int grid = 8 * p.rows_per_xcd;
-  hipLaunchKernelGGL(lite_attn_fwd_kernel<kQB>, dim3(grid), dim3(Geo<kQB>::kThreads), fwd_lds_bytes(), st, p);
+  // upper bound of the number of rows an XCD owns: ceil(chunks / 8) chunks of kChunkRows rows
+  const int BH = p.rows_total / p.Tq;
+  const int chunks = ((p.Tq + kChunkRows - 1) / kChunkRows) * BH;
+  const int per_xcd = ((chunks + 7) / 8) * kChunkRows;
+  hipLaunchKernelGGL(lite_attn_fwd_kernel<kQB>, dim3(8 * per_xcd), dim3(Geo<kQB>::kThreads), fwd_lds_bytes(), st, p);
   return hipGetLastError();
 }
 

@@ -50,6 +50,9 @@ _lib.lite_attn_mask_import.argtypes = [_H, ctypes.c_void_p, ctypes.c_size_t, cty
 _lib.lite_attn_skiplist_export.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p]
 _lib.lite_attn_profile.argtypes = [_H, ctypes.c_int]
 _lib.lite_attn_kernel_times.argtypes = [_H, ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
+_lib.lite_attn_mfma_peak.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_float),
+                                     ctypes.POINTER(ctypes.c_double)]
+_lib.lite_attn_mfma_peak.restype = ctypes.c_int
 _lib.lite_attn_free_mask.argtypes = [_H]
 _lib.lite_attn_free_mask.restype = None
 _lib.lite_attn_strerror.argtypes = [ctypes.c_int]
@@ -132,10 +135,19 @@ def lite_attn_profile(mask, enable: bool):
 
 
 def lite_attn_kernel_times(mask, step):
-    """-> (compaction_ms, attention_ms) of a completed step that ran with profiling enabled."""
+    """-> (prep_ms, attention_ms) of a completed step that ran with profiling enabled; prep = Skip-List compaction
+    + V transposition pre-pass."""
     a, b = ctypes.c_float(), ctypes.c_float()
     _check(_lib.lite_attn_kernel_times(mask, int(step), ctypes.byref(a), ctypes.byref(b)))
     return a.value, b.value
+
+
+def lite_attn_mfma_peak(hip_stream, dev_operands, iters=3000):
+    """-> sustained TFLOP/s of a register-resident bf16 MFMA loop on operands read from `dev_operands` (>= 64 KiB)."""
+    ms, fl = ctypes.c_float(), ctypes.c_double()
+    _check(_lib.lite_attn_mfma_peak(ctypes.c_void_p(int(hip_stream)), ctypes.c_void_p(int(dev_operands)), int(iters),
+                                    ctypes.byref(ms), ctypes.byref(fl)))
+    return fl.value / (ms.value * 1e-3) / 1e12
 
 
 def lite_attn_free_mask(mask):
