@@ -76,7 +76,8 @@ int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out);
 int lite_attn_set_stream(lite_attn_mask_t* mask, void* hip_stream);
 
 /* One attention call (Algorithm 2 with the deferred mask update, see top of file).
-     q, k, v   device bf16, layout given by the handle's strides; borrowed, not modified
+     q, k, v   device bf16, layout given by the handle's strides; borrowed, not modified; values must be finite
+               (the kernels are built with the assumption that no NaN occurs)
      out       device bf16, same layout; every valid row is written
      skip_mask handle; its mask is read (via the Skip-List built from it at the start of the call) and updated
      threshold signed -eps of eq. (sparge_cond) in natural-log units of S = QK^T/sqrt(d), must be < 0;
