@@ -64,7 +64,7 @@ typedef struct {
   uint64_t tiles_total;        /* B*H*Tq*Tk */
   uint64_t tiles_skipped_in;   /* tiles already marked when the step started (not visited) */
   uint64_t tiles_newly_marked; /* tiles the predicate marked during the step */
-  uint64_t live_list_bytes;    /* bytes of Skip-List entries the attention kernel consumed */
+  uint64_t live_list_bytes;    /* bytes of Skip-List entries (4 per run of live tiles) the attention kernel read */
 } lite_attn_stats_t;
 
 /* Allocates the handle and its device buffers on the current HIP device and clears the mask.
@@ -116,12 +116,21 @@ size_t lite_attn_mask_words(const lite_attn_mask_t* mask);
 int lite_attn_mask_export(lite_attn_mask_t* mask, uint64_t* host_bits, size_t words);
 int lite_attn_mask_import(lite_attn_mask_t* mask, const uint64_t* host_bits, size_t words, int next_step);
 
-/* Runs the Skip-List compaction on the current mask and copies the result to the host:
-     host_live_idx [B*H*Tq][Tk] uint16: for each Q-tile row the ascending indices of its live K/V tiles in the
-                                        first host_live_cnt[row] slots (the rest is unspecified)
+/* Runs the Skip-List compaction on the current mask and copies the result to the host.
+   Paper: the Skip-List is the run-length form of the mask that the loader walks -- consecutive non-skipped tiles are
+   one (start, end) pair (Implementation, "Producer and Skip-List Optimization").
+     host_runs  [B*H*Tq][lite_attn_skipruns_stride()] uint32: for each Q-tile row its maximal runs of live K/V tiles
+                in ascending order, entry = start | end << 16 (end exclusive), in the first host_nruns[row] slots
+     host_nruns [B*H*Tq] uint32
+   Synchronises. */
+int lite_attn_skipruns_export(lite_attn_mask_t* mask, uint32_t* host_runs, uint32_t* host_nruns);
+size_t lite_attn_skipruns_stride(const lite_attn_mask_t* mask); /* entries per row = ceil(Tk/2) */
+
+/* Same list expanded on the host into packed tile indices:
+     host_live_idx [B*H*Tq][Tk] uint16: ascending indices of the row's live K/V tiles in the first
+                                        host_live_cnt[row] slots (the rest is unspecified)
      host_live_cnt [B*H*Tq]     uint32
-   Paper: the Skip-List is the compressed form of the mask that the loader walks (Implementation, "Producer and
-   Skip-List Optimization"); here it is a packed index list rather than (start,end) runs.  Synchronises. */
+   Synchronises. */
 int lite_attn_skiplist_export(lite_attn_mask_t* mask, uint16_t* host_live_idx, uint32_t* host_live_cnt);
 
 void lite_attn_free_mask(lite_attn_mask_t* mask);

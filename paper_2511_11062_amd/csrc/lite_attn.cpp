@@ -12,14 +12,15 @@
 struct lite_attn_mask {
   lite_attn_desc_t desc;
   int Tq, Tk, W;
-  int live_stride;  // uint16 entries per Skip-List row (Tk rounded up to even)
+  int run_stride;   // capacity of one row's run-length Skip-List: a row of Tk tiles has at most ceil(Tk/2) runs
   int64_t rows;
   uint64_t* d_bits;
-  uint16_t* d_live_idx;
+  uint32_t* d_runs;   // [rows][run_stride] start | end << 16
+  uint32_t* d_nruns;  // [rows]
   uint32_t* d_live_cnt;
   uint32_t* d_order;  // [B*H][Tq] rows of each head ranked by Skip-List length
   uint16_t* d_vt;  // V^T scratch of the current call: [B*H][128][128*Tk] bf16
-  unsigned long long* d_stats;  // [max_steps][2]: skipped on entry, newly marked
+  unsigned long long* d_stats;  // [max_steps][3]: skipped on entry, newly marked, Skip-List runs
   hipStream_t stream;
   int next_step;
   bool profile;
@@ -79,24 +80,25 @@ int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out) {
   m->Tq = (desc->seqlen + desc->tile_q - 1) / desc->tile_q;
   m->Tk = (desc->seqlen + desc->tile_k - 1) / desc->tile_k;
   m->W = (m->Tk + 63) / 64;
-  m->live_stride = (m->Tk + 1) & ~1;
+  m->run_stride = (m->Tk + 1) / 2;
   m->rows = (int64_t)desc->batch * desc->heads * m->Tq;
   m->stream = nullptr;
   m->next_step = 0;
   m->profile = false;
   m->events = nullptr;
   m->timed = nullptr;
-  m->d_bits = nullptr; m->d_live_idx = nullptr; m->d_live_cnt = nullptr; m->d_stats = nullptr; m->d_vt = nullptr; m->d_order = nullptr;
+  m->d_bits = nullptr; m->d_runs = nullptr; m->d_nruns = nullptr; m->d_live_cnt = nullptr; m->d_stats = nullptr; m->d_vt = nullptr; m->d_order = nullptr;
   hipError_t e = hipMalloc(&m->d_bits, sizeof(uint64_t) * (size_t)m->rows * m->W);
-  if (e == hipSuccess) e = hipMalloc(&m->d_live_idx, sizeof(uint16_t) * (size_t)m->rows * m->live_stride);
+  if (e == hipSuccess) e = hipMalloc(&m->d_runs, sizeof(uint32_t) * (size_t)m->rows * m->run_stride);
+  if (e == hipSuccess) e = hipMalloc(&m->d_nruns, sizeof(uint32_t) * (size_t)m->rows);
   if (e == hipSuccess) e = hipMalloc(&m->d_live_cnt, sizeof(uint32_t) * (size_t)m->rows);
   if (e == hipSuccess) e = hipMalloc(&m->d_order, sizeof(uint32_t) * (size_t)m->rows);
   if (e == hipSuccess)
     e = hipMalloc(&m->d_vt, sizeof(uint16_t) * (size_t)desc->batch * desc->heads * 128 * ((size_t)m->Tk * 128));
-  if (e == hipSuccess) e = hipMalloc(&m->d_stats, sizeof(unsigned long long) * 2 * (size_t)desc->max_steps);
+  if (e == hipSuccess) e = hipMalloc(&m->d_stats, sizeof(unsigned long long) * 3 * (size_t)desc->max_steps);
   if (e == hipSuccess) e = la::prepare_fwd();
   if (e == hipSuccess)
-    e = la::launch_clear(m->d_bits, (size_t)m->rows * m->W, m->d_stats, 2 * (size_t)desc->max_steps, m->stream);
+    e = la::launch_clear(m->d_bits, (size_t)m->rows * m->W, m->d_stats, 3 * (size_t)desc->max_steps, m->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
   if (e != hipSuccess) {
     lite_attn_free_mask(m);
@@ -122,13 +124,13 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
   if (step != 0 && step != m->next_step) return LITE_ATTN_ESTEP;
   const lite_attn_desc_t& d = m->desc;
   if (step == 0)
-    LA_HIP(la::launch_clear(m->d_bits, (size_t)m->rows * m->W, m->d_stats, 2 * (size_t)d.max_steps, m->stream));
-  unsigned long long* st = m->d_stats + 2 * (size_t)step;
+    LA_HIP(la::launch_clear(m->d_bits, (size_t)m->rows * m->W, m->d_stats, 3 * (size_t)d.max_steps, m->stream));
+  unsigned long long* st = m->d_stats + 3 * (size_t)step;
   hipEvent_t* ev = (m->profile && m->events) ? m->events + 3 * (size_t)step : nullptr;
   if (m->timed) m->timed[step] = ev != nullptr;
   if (ev) LA_HIP(hipEventRecord(ev[0], m->stream));
-  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->live_stride, m->d_live_idx, m->d_live_cnt, st,
-                            m->stream));
+  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->run_stride, m->d_runs, m->d_nruns,
+                            m->d_live_cnt, st, st + 2, m->stream));
   LA_HIP(la::launch_order_rows(m->d_live_cnt, d.batch * d.heads, m->Tq, m->Tk, m->d_order, m->stream));
   LA_HIP(la::launch_transpose_v(static_cast<const uint16_t*>(v), m->d_vt, d.stride_b, d.stride_h, d.stride_n,
                                 d.batch * d.heads, d.heads, d.seqlen, m->Tk, m->stream));
@@ -139,7 +141,8 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
   p.out = static_cast<uint16_t*>(out);
   p.stride_b = d.stride_b; p.stride_h = d.stride_h; p.stride_n = d.stride_n;
   p.H = d.heads; p.N = d.seqlen; p.Tq = m->Tq; p.Tk = m->Tk; p.W = m->W;
-  p.live_idx = m->d_live_idx; p.live_stride = m->live_stride; p.live_cnt = m->d_live_cnt; p.bits = m->d_bits;
+  p.runs = m->d_runs; p.run_stride = m->run_stride; p.nruns = m->d_nruns; p.live_cnt = m->d_live_cnt;
+  p.bits = m->d_bits;
   p.stat_newly = st + 1;
   p.thr = threshold;
   p.scale = 1.0f / std::sqrt((float)d.head_dim);
@@ -156,14 +159,14 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
 int lite_attn_skip_stats(lite_attn_mask_t* m, int step, lite_attn_stats_t* host_out) {
   if (!m || !host_out) return LITE_ATTN_EINVAL;
   if (step < 0 || step >= m->next_step || step >= m->desc.max_steps) return LITE_ATTN_ESTEP;
-  unsigned long long raw[2];
-  LA_HIP(hipMemcpyAsync(raw, m->d_stats + 2 * (size_t)step, sizeof raw, hipMemcpyDeviceToHost, m->stream));
+  unsigned long long raw[3];
+  LA_HIP(hipMemcpyAsync(raw, m->d_stats + 3 * (size_t)step, sizeof raw, hipMemcpyDeviceToHost, m->stream));
   LA_HIP(hipStreamSynchronize(m->stream));
   host_out->step = step;
   host_out->tiles_total = (uint64_t)m->rows * (uint64_t)m->Tk;
   host_out->tiles_skipped_in = raw[0];
   host_out->tiles_newly_marked = raw[1];
-  host_out->live_list_bytes = (host_out->tiles_total - raw[0]) * sizeof(uint16_t);
+  host_out->live_list_bytes = raw[2] * sizeof(uint32_t);
   return LITE_ATTN_OK;
 }
 
@@ -248,23 +251,44 @@ int lite_attn_mask_import(lite_attn_mask_t* m, const uint64_t* host_bits, size_t
   return LITE_ATTN_OK;
 }
 
-int lite_attn_skiplist_export(lite_attn_mask_t* m, uint16_t* host_live_idx, uint32_t* host_live_cnt) {
-  if (!m || !host_live_idx || !host_live_cnt) return LITE_ATTN_EINVAL;
-  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->live_stride, m->d_live_idx, m->d_live_cnt,
-                            nullptr, m->stream));
-  LA_HIP(hipMemcpy2DAsync(host_live_idx, sizeof(uint16_t) * (size_t)m->Tk, m->d_live_idx,
-                          sizeof(uint16_t) * (size_t)m->live_stride, sizeof(uint16_t) * (size_t)m->Tk, (size_t)m->rows,
-                          hipMemcpyDeviceToHost, m->stream));
-  LA_HIP(hipMemcpyAsync(host_live_cnt, m->d_live_cnt, sizeof(uint32_t) * (size_t)m->rows, hipMemcpyDeviceToHost,
-                        m->stream));
+int lite_attn_skipruns_export(lite_attn_mask_t* m, uint32_t* host_runs, uint32_t* host_nruns) {
+  if (!m || !host_runs || !host_nruns) return LITE_ATTN_EINVAL;
+  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->run_stride, m->d_runs, m->d_nruns, m->d_live_cnt,
+                            nullptr, nullptr, m->stream));
+  LA_HIP(hipMemcpyAsync(host_runs, m->d_runs, sizeof(uint32_t) * (size_t)m->rows * m->run_stride,
+                        hipMemcpyDeviceToHost, m->stream));
+  LA_HIP(hipMemcpyAsync(host_nruns, m->d_nruns, sizeof(uint32_t) * (size_t)m->rows, hipMemcpyDeviceToHost, m->stream));
   LA_HIP(hipStreamSynchronize(m->stream));
   return LITE_ATTN_OK;
+}
+
+size_t lite_attn_skipruns_stride(const lite_attn_mask_t* m) { return m ? (size_t)m->run_stride : 0; }
+
+int lite_attn_skiplist_export(lite_attn_mask_t* m, uint16_t* host_live_idx, uint32_t* host_live_cnt) {
+  if (!m || !host_live_idx || !host_live_cnt) return LITE_ATTN_EINVAL;
+  uint32_t* runs = new (std::nothrow) uint32_t[(size_t)m->rows * m->run_stride];
+  uint32_t* nruns = new (std::nothrow) uint32_t[(size_t)m->rows];
+  int rc = (runs && nruns) ? lite_attn_skipruns_export(m, runs, nruns) : LITE_ATTN_ENOMEM;
+  if (rc == LITE_ATTN_OK) {
+    for (int64_t row = 0; row < m->rows; ++row) {  // expand the runs into the packed index list
+      uint32_t n = 0;
+      for (uint32_t x = 0; x < nruns[row]; ++x) {
+        const uint32_t e = runs[row * m->run_stride + x];
+        for (uint32_t j = e & 0xffffu; j < (e >> 16); ++j) host_live_idx[row * m->Tk + n++] = (uint16_t)j;
+      }
+      host_live_cnt[row] = n;
+    }
+  }
+  delete[] runs;
+  delete[] nruns;
+  return rc;
 }
 
 void lite_attn_free_mask(lite_attn_mask_t* m) {
   if (!m) return;
   if (m->d_bits) (void)hipFree(m->d_bits);
-  if (m->d_live_idx) (void)hipFree(m->d_live_idx);
+  if (m->d_runs) (void)hipFree(m->d_runs);
+  if (m->d_nruns) (void)hipFree(m->d_nruns);
   if (m->d_live_cnt) (void)hipFree(m->d_live_cnt);
   if (m->d_stats) (void)hipFree(m->d_stats);
   if (m->d_vt) (void)hipFree(m->d_vt);

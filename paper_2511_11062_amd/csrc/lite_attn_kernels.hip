@@ -1,7 +1,7 @@
 // gfx950 (CDNA4) kernels of the LiteAttention forward path.
 //
 //   clear_state_kernel   : zero the Skip-Mask and the statistics (step 0)
-//   compact_skiplist     : Skip-Mask row -> packed ascending list of live K/V tile indices
+//   compact_skiplist     : Skip-Mask row -> run-length list of its live K/V tiles, (start,end) per run
 //                          (Implementation, "Producer and Skip-List Optimization")
 //   lite_attn_fwd_kernel : fused tiled forward over the live tiles with the skip predicate
 //                          (Algorithm 2; eq. sparge_cond; tile recurrences of the Preliminaries)
@@ -55,29 +55,47 @@ __global__ void clear_state_kernel(uint64_t* bits, size_t words, unsigned long l
   for (size_t x = i; x < nstats; x += stride) stats[x] = 0;
 }
 
-// One wave per Q-tile row: ballot + prefix popcount packs the indices of clear bits.
+// Skip-List compaction, one wave per Q-tile row.  The list is run-length encoded as the paper describes: one entry
+// (start | end << 16) per maximal run of consecutive live K/V tiles [start, end).  Lane l looks at bit l of each
+// 64-tile word: a live tile whose predecessor is not live starts a run, one whose successor is not live ends it;
+// the k-th start and the k-th end of a row belong to the same run, so the two 16-bit halves are written
+// independently at the position given by a ballot + prefix popcount.
 __global__ __launch_bounds__(256) void compact_skiplist(const uint64_t* __restrict__ bits, int rows, int Tk, int W,
-                                                         int live_stride, uint16_t* __restrict__ live_idx,
-                                                         uint32_t* __restrict__ live_cnt,
-                                                         unsigned long long* __restrict__ stat_skipped_in) {
+                                                         int run_stride, uint32_t* __restrict__ runs,
+                                                         uint32_t* __restrict__ nruns, uint32_t* __restrict__ live_cnt,
+                                                         unsigned long long* __restrict__ stat_skipped_in,
+                                                         unsigned long long* __restrict__ stat_runs) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
   const uint64_t* mrow = bits + (size_t)row * W;
-  uint16_t* out = live_idx + (size_t)row * live_stride;
-  uint32_t n = 0;
+  uint16_t* out = reinterpret_cast<uint16_t*>(runs + (size_t)row * run_stride);
+  auto live_word = [&](int w) -> uint64_t {  // bit l set = tile 64w+l exists and is not skipped
+    if (w < 0 || w >= W) return 0ull;
+    const int valid = Tk - 64 * w;
+    return ~mrow[w] & (valid >= 64 ? ~0ull : ((1ull << valid) - 1ull));
+  };
+  uint32_t ns = 0, ne = 0, n = 0;
+  uint64_t prev = 0ull, cur = live_word(0);
   for (int w = 0; w < W; ++w) {
-    const uint64_t word = mrow[w];
-    const int j = w * 64 + lane;
-    const bool live = (j < Tk) && !((word >> lane) & 1ull);
-    const uint64_t bal = __ballot(live);
-    const uint32_t pre = __popcll(bal & ((1ull << lane) - 1ull));
-    if (live) out[n + pre] = (uint16_t)j;
-    n += __popcll(bal);
+    const uint64_t next = live_word(w + 1);
+    const uint64_t starts = cur & ~((cur << 1) | (prev >> 63));
+    const uint64_t ends = cur & ~((cur >> 1) | (next << 63));
+    const uint64_t below = (1ull << lane) - 1ull;
+    const int j = 64 * w + lane;
+    if ((starts >> lane) & 1ull) out[2 * (ns + __popcll(starts & below))] = (uint16_t)j;
+    if ((ends >> lane) & 1ull) out[2 * (ne + __popcll(ends & below)) + 1] = (uint16_t)(j + 1);
+    ns += __popcll(starts);
+    ne += __popcll(ends);
+    n += __popcll(cur);
+    prev = cur;
+    cur = next;
   }
   if (lane == 0) {
+    nruns[row] = ns;
     live_cnt[row] = n;
     if (stat_skipped_in && (uint32_t)Tk > n) atomicAdd(stat_skipped_in, (unsigned long long)(Tk - n));
+    if (stat_runs && ns) atomicAdd(stat_runs, (unsigned long long)ns);
   }
 }
 
@@ -443,7 +461,8 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
   const int cnt = (int)p.live_cnt[row];
   // the Skip-List is read-only here: constant address space makes these wave-uniform reads scalar loads
   typedef const __attribute__((address_space(4))) uint32_t* const_u32_ptr;
-  const_u32_ptr live32 = (const_u32_ptr)(p.live_idx + (size_t)row * p.live_stride);
+  const_u32_ptr runs = (const_u32_ptr)(p.runs + (size_t)row * p.run_stride);
+  const int nruns = (int)p.nruns[row];
   int* flags = reinterpret_cast<int*>(smem + kFlagsOff);
 
   Lane<QB> ln;
@@ -504,14 +523,29 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
   int* flag_slot1 = lane == 0 ? flags + 4 + wave : flags + 8 + lane;
 
   if (cnt > 0) {
-    auto tile_at = [&](int t) -> int {
-      const uint32_t w = live32[t >> 1];
-      return (int)((t & 1) ? (w >> 16) : (w & 0xffffu));
+    // Walk the run-length Skip-List with a cursor kept two tiles ahead of the tile being computed, so that the
+    // scalar load of the next run entry is off the critical path.  At the end of the list the cursor stays put.
+    int c_run = 0, c_j, c_end;
+    {
+      const uint32_t e = runs[0];
+      c_j = (int)(e & 0xffffu);
+      c_end = (int)(e >> 16);
+    }
+    auto advance = [&]() {
+      if (c_j + 1 < c_end) {
+        ++c_j;
+      } else if (c_run + 1 < nruns) {
+        ++c_run;
+        const uint32_t e = runs[c_run];
+        c_j = (int)(e & 0xffffu);
+        c_end = (int)(e >> 16);
+      }
     };
-    int j_cur = tile_at(0);
-    int j_nxt = tile_at(min(1, cnt - 1));
+    int j_cur = c_j;
+    advance();
+    int j_nxt = c_j;
     // the last live tile needs column masking if it is the ragged last tile of the sequence
-    const bool tail = (N & (kTile - 1)) != 0 && tile_at(cnt - 1) == p.Tk - 1;
+    const bool tail = (N & (kTile - 1)) != 0 && (int)(runs[nruns - 1] >> 16) == p.Tk;
     const int n_main = tail ? cnt - 1 : cnt;
 
     // prologue: the odd V^T buffer is read (times P~ = 0) before it is first filled: make it finite; K of
@@ -541,7 +575,8 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
       }
     };
     for (int t = 0; t < n_main; ++t) {
-      const int j_nn = tile_at(min(t + 2, cnt - 1));  // needed one tile from now: its latency is hidden
+      advance();
+      const int j_nn = c_j;  // needed one tile from now
       int* fs = (t & 1) ? flag_slot1 : flag_slot0;
       stage<QB, 0, false>(st, ln, smem, j_cur, j_nxt, fs);
       stage<QB, 1, false>(st, ln, smem, j_cur, j_nxt, fs);
@@ -633,10 +668,11 @@ hipError_t launch_clear(uint64_t* bits, size_t words, unsigned long long* stats,
   return hipGetLastError();
 }
 
-hipError_t launch_compact(const uint64_t* bits, int rows, int Tk, int W, int live_stride, uint16_t* live_idx,
-                          uint32_t* live_cnt, unsigned long long* stat_skipped_in, hipStream_t st) {
-  hipLaunchKernelGGL(compact_skiplist, dim3((rows + 3) / 4), dim3(256), 0, st, bits, rows, Tk, W, live_stride,
-                     live_idx, live_cnt, stat_skipped_in);
+hipError_t launch_compact(const uint64_t* bits, int rows, int Tk, int W, int run_stride, uint32_t* runs,
+                          uint32_t* nruns, uint32_t* live_cnt, unsigned long long* stat_skipped_in,
+                          unsigned long long* stat_runs, hipStream_t st) {
+  hipLaunchKernelGGL(compact_skiplist, dim3((rows + 3) / 4), dim3(256), 0, st, bits, rows, Tk, W, run_stride, runs,
+                     nruns, live_cnt, stat_skipped_in, stat_runs);
   return hipGetLastError();
 }
 

@@ -48,6 +48,10 @@ _lib.lite_attn_mask_words.restype = ctypes.c_size_t
 _lib.lite_attn_mask_export.argtypes = [_H, ctypes.c_void_p, ctypes.c_size_t]
 _lib.lite_attn_mask_import.argtypes = [_H, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
 _lib.lite_attn_skiplist_export.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p]
+_lib.lite_attn_skipruns_export.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p]
+_lib.lite_attn_skipruns_export.restype = ctypes.c_int
+_lib.lite_attn_skipruns_stride.argtypes = [_H]
+_lib.lite_attn_skipruns_stride.restype = ctypes.c_size_t
 _lib.lite_attn_profile.argtypes = [_H, ctypes.c_int]
 _lib.lite_attn_kernel_times.argtypes = [_H, ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
 _lib.lite_attn_mfma_peak.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_float),
@@ -148,6 +152,15 @@ def lite_attn_mfma_peak(hip_stream, dev_operands, iters=3000):
     _check(_lib.lite_attn_mfma_peak(ctypes.c_void_p(int(hip_stream)), ctypes.c_void_p(int(dev_operands)), int(iters),
                                     ctypes.byref(ms), ctypes.byref(fl)))
     return fl.value / (ms.value * 1e-3) / 1e12
+
+
+def lite_attn_skipruns_export(mask, rows: int):
+    """-> (runs uint32 [rows, stride] with start | end << 16 per run, nruns uint32 [rows]) of the current mask."""
+    stride = int(_lib.lite_attn_skipruns_stride(mask))
+    runs = np.empty((rows, stride), dtype=np.uint32)
+    nruns = np.empty(rows, dtype=np.uint32)
+    _check(_lib.lite_attn_skipruns_export(mask, runs.ctypes.data, nruns.ctypes.data))
+    return runs, nruns
 
 
 def lite_attn_free_mask(mask):

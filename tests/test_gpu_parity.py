@@ -67,6 +67,15 @@ def test_skiplist_compaction_matches_host_reference():
                 for r in range(B * H * Tq):
                     assert np.array_equal(idx[r, :cnt[r]], np.flatnonzero(mask[r] == 0))
                 assert np.array_equal(parity.unpack_mask(la.lite_attn_mask_export(h).reshape(-1, -(-Tk // 64)), Tk), mask)
+                # the run-length form: maximal runs of live tiles, ascending, (start, end) with end exclusive
+                runs, nruns = la.lite_attn_skipruns_export(h, B * H * Tq)
+                for r in range(B * H * Tq):
+                    live = np.concatenate(([0], (mask[r] == 0).astype(np.int8), [0]))
+                    edges = np.flatnonzero(np.diff(live))
+                    starts, ends = edges[0::2], edges[1::2]
+                    assert nruns[r] == len(starts)
+                    assert np.array_equal(runs[r, :nruns[r]] & 0xffff, starts)
+                    assert np.array_equal(runs[r, :nruns[r]] >> 16, ends)
         finally:
             la.lite_attn_free_mask(h)
 
