@@ -124,3 +124,22 @@ def test_fully_masked_row_gives_zero_output():
         assert torch.isfinite(o).all() and o[0, 0, 128:].abs().max() > 0
     finally:
         la.lite_attn_free_mask(h)
+
+
+def test_threshold_schedule_driver_meets_its_error_bounds():
+    """Accumulated-Error Calibration on the tiny workload: three segments with bounds xi-tau, xi, xi+tau."""
+    from paper_2511_11062_amd import calibrate
+    wl = inputs.Workload("cal", 1, 2, (2, 32, 32), steps=6, seed=31)
+    seq = inputs.DriftSequence(wl, "cuda:0")
+    data = [next(seq) for _ in range(6)]
+    sched = calibrate.calibrate(wl, data, xi=0.075, tau=0.02)
+    assert [round(s["bound"], 3) for s in sched] == [0.055, 0.055, 0.075, 0.075, 0.095, 0.095]
+    skipped = [s["skipped_after"] for s in sched]
+    assert skipped == sorted(skipped) and skipped[-1] > 0.05          # the mask only grows, and something is skipped
+    assert sched[0]["met"] and sched[0]["threshold"] > -12.0
+    for s in sched:
+        assert -12.0 <= s["threshold"] <= -0.05
+        # the inherited mask can already exceed a step's bound as the inputs drift (bits are never cleared); the
+        # driver then marks as little as it can (the most negative threshold) and says so
+        assert (s["eta"] <= s["bound"]) == s["met"]
+        assert s["met"] or s["threshold"] == -12.0
