@@ -18,7 +18,8 @@
  *   - deferral of a freshly fired bit to the next timestep (the tile is still
  *     accumulated in the step that marks it): Implementation, "Skip-Mask
  *     Evaluation Mechanism" and "Producer and Skip-List Optimization";
- *   - linear order of the j loop: Experiments, "Settings".
+ *   - linear order of the j loop: Experiments, "Settings"; optionally another visiting order given as an
+ *     explicit permutation per Q tile (Method, "Skipping Condition": other orders reach the global maximum sooner).
  * The row-sum l and the final division are the textbook online softmax the
  * paper leaves out "for brevity".
  *
@@ -76,7 +77,8 @@ static int intersects(int64_t lo, int64_t hi, int64_t ps, int64_t pl) {
 
 /* One Q-tile row (b,h,i): Algorithm 2 with the deferred / immediate reading. */
 static int oracle_row(const la_oracle_shape* sh, const uint16_t* q, const uint16_t* k, const uint16_t* v,
-                      uint8_t* mask_row, real thr, real* out_bh, real* g_row, int b, int h, int i) {
+                      uint8_t* mask_row, real thr, real* out_bh, real* g_row, int b, int h, int i,
+                      const int32_t* visit) {
   const int d = sh->head_dim, hq = sh->tile_q, hk = sh->tile_k, N = sh->seqlen;
   const int Tk = (N + hk - 1) / hk;
   const int r0 = i * hq;
@@ -104,8 +106,9 @@ static int oracle_row(const la_oracle_shape* sh, const uint16_t* q, const uint16
   }
   const int q_pinned = intersects(r0, r0 + nr, sh->protect_start, sh->protect_len);
 
-  for (int j = 0; j < Tk; ++j) { /* linear order */
-    if (mask_row[j]) {           /* SkipMask(i,j): nothing of tile j is touched */
+  for (int t = 0; t < Tk; ++t) {
+    const int j = visit ? visit[t] : t; /* linear order unless a visiting order is given */
+    if (mask_row[j]) {                  /* SkipMask(i,j): nothing of tile j is touched */
       if (g_row) g_row[j] = (real)NAN;
       continue;
     }
@@ -169,9 +172,12 @@ static int oracle_row(const la_oracle_shape* sh, const uint16_t* q, const uint16
  *   out    [B,H,N,d] contiguous `real`; only the rows computed are written
  *   g      [B,H,Tq,Tk] predicate value of every evaluated tile, NaN for tiles skipped on entry; may be NULL
  *   rows   optional list of flattened row ids (b*H+h)*Tq+i to compute; NULL = every row
+ *   visit  optional [Tq][Tk] int32: visit[i][t] = K/V tile visited t-th by Q tile i (a permutation of 0..Tk-1,
+ *          the same for every batch entry and head); NULL = ascending
  */
 int la_oracle_step(const la_oracle_shape* sh, const uint16_t* q, const uint16_t* k, const uint16_t* v,
-                   uint8_t* mask, real thr, real* out, real* g, const int64_t* rows, int64_t nrows) {
+                   uint8_t* mask, real thr, real* out, real* g, const int64_t* rows, int64_t nrows,
+                   const int32_t* visit) {
   if (!sh || !q || !k || !v || !mask || !out) return LA_ORACLE_EINVAL;
   if (sh->batch < 1 || sh->heads < 1 || sh->seqlen < 1 || sh->head_dim < 1 || sh->tile_q < 1 || sh->tile_k < 1)
     return LA_ORACLE_EINVAL;
@@ -193,7 +199,7 @@ int la_oracle_step(const la_oracle_shape* sh, const uint16_t* q, const uint16_t*
     int h = (int)((row / Tq) % H);
     int b = (int)(row / ((int64_t)Tq * H));
     int rc = oracle_row(sh, q, k, v, mask + row * Tk, thr, out + ((int64_t)b * H + h) * N * d,
-                        g ? g + row * Tk : NULL, b, h, i);
+                        g ? g + row * Tk : NULL, b, h, i, visit ? visit + (int64_t)i * Tk : NULL);
     if (rc != LA_ORACLE_OK) {
 #pragma omp critical
       status = rc;

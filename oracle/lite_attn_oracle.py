@@ -57,7 +57,7 @@ def load_library(path: str, f64: bool):
     lib.la_oracle_step.restype = ctypes.c_int
     lib.la_oracle_step.argtypes = [
         ctypes.POINTER(_Shape), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-        ctypes.c_void_p, real, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
+        ctypes.c_void_p, real, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
     lib.la_oracle_real_bytes.restype = ctypes.c_int
     assert lib.la_oracle_real_bytes() == (8 if f64 else 4)
     return lib
@@ -71,6 +71,11 @@ def _load(f64: bool):
         return _LIBS[f64]
 
 
+def diagonal_first(tq: int, tk: int) -> np.ndarray:
+    """Visiting order that starts at the diagonal tile and wraps around: i, i+1, ..., Tk-1, 0, ..., i-1."""
+    return ((np.arange(tq)[:, None] + np.arange(tk)[None, :]) % tk).astype(np.int32)
+
+
 def threads() -> int:
     """Number of OpenMP threads the oracle will use (for the benchmark's `cores` field)."""
     env = os.environ.get("OMP_NUM_THREADS")
@@ -80,7 +85,7 @@ def threads() -> int:
 
 
 def oracle_step(q, k, v, mask, thr, *, tile_q=128, tile_k=128, protect=(0, 0), immediate=False,
-                rows=None, f64=False, out=None, libs=None):
+                rows=None, f64=False, out=None, libs=None, visit=None):
     """One attention call of the oracle.
 
     q, k, v : uint16 numpy arrays [B,H,N,d] holding bf16 bit patterns (any strides with d contiguous).
@@ -88,6 +93,7 @@ def oracle_step(q, k, v, mask, thr, *, tile_q=128, tile_k=128, protect=(0, 0), i
     thr     : signed threshold (-eps), natural-log units of S; ``-inf`` never fires.
     rows    : optional iterable of flattened row ids (b*H+h)*Tq+i; other rows of `out`/`g` stay NaN
               and their mask rows are returned unchanged.
+    visit   : optional int32 [Tq,Tk], visit[i,t] = K/V tile that Q tile i visits t-th (default: ascending).
     Returns (out [B,H,N,d] real, mask_exit uint8, g [B,H,Tq,Tk] real with NaN for unevaluated tiles).
     """
     lib = libs[f64] if libs is not None else _load(f64)
@@ -107,10 +113,15 @@ def oracle_step(q, k, v, mask, thr, *, tile_q=128, tile_k=128, protect=(0, 0), i
     rows_arr = None
     if rows is not None:
         rows_arr = np.ascontiguousarray(np.asarray(list(rows), dtype=np.int64))
+    visit_arr = None
+    if visit is not None:
+        visit_arr = np.ascontiguousarray(visit, dtype=np.int32)
+        assert visit_arr.shape == (Tq, Tk) and (np.sort(visit_arr, axis=1) == np.arange(Tk)).all()
     rc = lib.la_oracle_step(ctypes.byref(sh), q.ctypes.data, k.ctypes.data, v.ctypes.data,
                             mask_exit.ctypes.data, float(thr), out.ctypes.data, g.ctypes.data,
                             rows_arr.ctypes.data if rows_arr is not None else None,
-                            0 if rows_arr is None else rows_arr.size)
+                            0 if rows_arr is None else rows_arr.size,
+                            visit_arr.ctypes.data if visit_arr is not None else None)
     if rc != 0:
         raise ValueError("la_oracle_step failed with code %d" % rc)
     return out, mask_exit, g

@@ -29,7 +29,7 @@ def expand_tiles(live, tq, tk, n):
     return np.repeat(np.repeat(live, tq, axis=0), tk, axis=1)[:n, :n]
 
 
-def predicate_values(q, k, entry_mask, tq, tk):
+def predicate_values(q, k, entry_mask, tq, tk, visit=None):
     """g_ij of eq. (sparge_cond) for every tile live on entry, from the dense S: R[r,j] = max of S over
     the columns of tile j; the cumulative max m_ij is the max of R over live tiles up to j; g_ij is the
     max over the tile's rows of R[r,j] - m_ij[r].  NaN for tiles skipped on entry."""
@@ -42,9 +42,10 @@ def predicate_values(q, k, entry_mask, tq, tk):
     g = np.full((Tq, Tk), np.nan)
     for i in range(Tq):
         rows = slice(i * tq, min(n, (i + 1) * tq))
-        Ri = np.where(entry_mask[i][None, :] != 0, -np.inf, R[rows])     # skipped tiles are never seen
+        order = np.arange(Tk) if visit is None else np.asarray(visit[i])  # the cumulative max follows the visiting order
+        Ri = np.where(entry_mask[i][None, :] != 0, -np.inf, R[rows])[:, order]   # skipped tiles are never seen
         cum = np.maximum.accumulate(Ri, axis=1)
         with np.errstate(invalid="ignore"):                              # -inf - -inf on skipped tiles
             diff = (Ri - cum).max(axis=0)
-        g[i] = np.where(entry_mask[i] != 0, np.nan, diff)
+        g[i, order] = np.where(entry_mask[i][order] != 0, np.nan, diff)
     return g

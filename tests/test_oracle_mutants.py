@@ -31,6 +31,8 @@ MUTANTS = [
     ("running_max_not_updated", "m[r] = mnew[r];\n", ";\n"),
     ("tail_columns_ignored", "const int nc = (N - c0 < hk) ? (N - c0) : hk;", "const int nc = hk; if (c0 + nc > N) continue;"),
     ("stride_h_as_stride_b", "(int64_t)h * sh->stride_h;", "(int64_t)h * sh->stride_b;"),
+    ("visiting_order_ignored", "const int j = visit ? visit[t] : t;", "const int j = t;"),
+    ("visiting_order_of_row_zero", "visit ? visit + (int64_t)i * Tk : NULL", "visit"),
 ]
 
 PINS = [
@@ -45,6 +47,7 @@ PINS = [
     pins.test_mask_evolution_invariants,
     pins.test_pinned_tiles_never_fire,
     pins.test_first_tile_never_fires_when_all_scores_are_negative,
+    pins.test_visiting_order,
 ]
 
 

@@ -219,6 +219,36 @@ def test_first_tile_never_fires_when_all_scores_are_negative():
         assert g[0, 0, i, first] == 0.0 and mexit[0, 0, i, first] == 0
 
 
+def test_visiting_order():
+    """Another j order (Method, "Skipping Condition"): the output with the threshold disabled does not depend on it
+    (softmax is order-free); the predicate values follow the cumulative max along the given order; starting at the
+    diagonal finds the row maximum at once on locality-structured inputs, so more tiles fire.
+    Catches: the order applied to the data but not to the mask index, or the running max still taken in ascending j."""
+    from oracle.lite_attn_oracle import diagonal_first
+    H, N, d, t = 2, 512, 32, 64
+    (q, k, v), = _drift_steps(12, H, N, d, 1)
+    T = N // t
+    rng = np.random.default_rng(12)
+    for visit in (diagonal_first(T, T), np.stack([rng.permutation(T) for _ in range(T)]).astype(np.int32)):
+        m0 = empty_mask(1, H, N, t, t)
+        o_lin, _, _ = oracle_step(q, k, v, m0, NINF, tile_q=t, tile_k=t, f64=True)
+        o_vis, _, _ = oracle_step(q, k, v, m0, NINF, tile_q=t, tile_k=t, f64=True, visit=visit)
+        assert np.abs(o_lin - o_vis).max() <= 1e-12
+        entry = (rng.random((1, H, T, T)) < 0.2).astype(np.uint8)
+        entry[0, :, np.arange(T), np.arange(T)] = 0
+        thr = -1.0
+        _, mexit, g = oracle_step(q, k, v, entry, thr, tile_q=t, tile_k=t, f64=True, visit=visit)
+        for h in range(H):
+            gb = brute.predicate_values(brute.widen(q[0, h]), brute.widen(k[0, h]), entry[0, h], t, t, visit=visit)
+            assert np.array_equal(np.isnan(g[0, h]), np.isnan(gb)) and np.nanmax(np.abs(g[0, h] - gb)) <= 1e-12
+            fired = np.where(np.isnan(gb), False, gb <= thr)
+            assert np.array_equal(mexit[0, h] != 0, (entry[0, h] != 0) | fired)
+    m0 = empty_mask(1, H, N, t, t)
+    _, m_lin, _ = oracle_step(q, k, v, m0, -1.0, tile_q=t, tile_k=t)
+    _, m_diag, _ = oracle_step(q, k, v, m0, -1.0, tile_q=t, tile_k=t, visit=diagonal_first(T, T))
+    assert m_diag.sum() > m_lin.sum() > 0
+
+
 def test_pinned_tiles_never_fire():
     """Tiles whose Q rows or K/V columns intersect the protected token range are evaluated but never
     marked (benchmark requirement for text tokens; not from the paper)."""
