@@ -42,6 +42,12 @@ typedef enum {
   LITE_ATTN_EHIP = -5          /* a HIP runtime call failed; lite_attn_last_hip_error() has its code */
 } lite_attn_error;
 
+/* desc.flags.  The skip predicate compares a tile with the running row maximum over the tiles visited BEFORE it, so
+   the visiting order of the j loop decides how soon tiles can be judged against the true maximum (paper: Method,
+   "Skipping Condition": other orderings reach the global maximum faster; its experiments use the linear order).
+   Default: ascending j.  LITE_ATTN_ORDER_DIAGONAL_FIRST: Q tile i visits K/V tiles i, i+1, ..., Tk-1, 0, ..., i-1. */
+#define LITE_ATTN_ORDER_DIAGONAL_FIRST 1
+
 /* Shape of one attention layer; fixed for the life of a handle. */
 typedef struct {
   int32_t batch, heads, seqlen, head_dim; /* head_dim must be 128 */
@@ -50,7 +56,7 @@ typedef struct {
                                              [B,H,N,d]: (H*N*d, N*d, d);  [B,N,H,d]: (N*H*d, d, H*d) */
   int32_t protect_start, protect_len;     /* token range [start, start+len) never skipped: a tile whose Q rows or
                                              K/V columns intersect it is evaluated but never marked; len 0 = none */
-  int32_t flags;                          /* must be 0 (reserved) */
+  int32_t flags;                          /* 0, or LITE_ATTN_ORDER_DIAGONAL_FIRST */
   int32_t max_steps;                      /* capacity of the per-step statistics, >= 1 */
 } lite_attn_desc_t;
 
@@ -120,14 +126,14 @@ int lite_attn_mask_import(lite_attn_mask_t* mask, const uint64_t* host_bits, siz
    Paper: the Skip-List is the run-length form of the mask that the loader walks -- consecutive non-skipped tiles are
    one (start, end) pair (Implementation, "Producer and Skip-List Optimization").
      host_runs  [B*H*Tq][lite_attn_skipruns_stride()] uint32: for each Q-tile row its maximal runs of live K/V tiles
-                in ascending order, entry = start | end << 16 (end exclusive), in the first host_nruns[row] slots
+                in visiting order, entry = start | end << 16 (end exclusive), in the first host_nruns[row] slots
      host_nruns [B*H*Tq] uint32
    Synchronises. */
 int lite_attn_skipruns_export(lite_attn_mask_t* mask, uint32_t* host_runs, uint32_t* host_nruns);
 size_t lite_attn_skipruns_stride(const lite_attn_mask_t* mask); /* entries per row = ceil(Tk/2) */
 
 /* Same list expanded on the host into packed tile indices:
-     host_live_idx [B*H*Tq][Tk] uint16: ascending indices of the row's live K/V tiles in the first
+     host_live_idx [B*H*Tq][Tk] uint16: indices of the row's live K/V tiles, in visiting order, in the first
                                         host_live_cnt[row] slots (the rest is unspecified)
      host_live_cnt [B*H*Tq]     uint32
    Synchronises. */

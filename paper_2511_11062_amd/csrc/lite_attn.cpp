@@ -47,7 +47,7 @@ int check_desc(const lite_attn_desc_t* d) {
   if (!d) return LITE_ATTN_EINVAL;
   if (d->batch < 1 || d->heads < 1 || d->seqlen < 1 || d->head_dim < 1 || d->tile_q < 1 || d->tile_k < 1)
     return LITE_ATTN_EINVAL;
-  if (d->max_steps < 1 || d->flags != 0) return LITE_ATTN_EINVAL;
+  if (d->max_steps < 1 || (d->flags & ~LITE_ATTN_ORDER_DIAGONAL_FIRST) != 0) return LITE_ATTN_EINVAL;
   if (d->protect_len < 0 || d->protect_start < 0 ||
       (d->protect_len > 0 && (int64_t)d->protect_start + d->protect_len > d->seqlen))
     return LITE_ATTN_EINVAL;
@@ -129,8 +129,8 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
   hipEvent_t* ev = (m->profile && m->events) ? m->events + 3 * (size_t)step : nullptr;
   if (m->timed) m->timed[step] = ev != nullptr;
   if (ev) LA_HIP(hipEventRecord(ev[0], m->stream));
-  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->run_stride, m->d_runs, m->d_nruns,
-                            m->d_live_cnt, st, st + 2, m->stream));
+  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tq, m->Tk, m->W, d.flags & LITE_ATTN_ORDER_DIAGONAL_FIRST, m->run_stride,
+                            m->d_runs, m->d_nruns, m->d_live_cnt, st, st + 2, m->stream));
   LA_HIP(la::launch_order_rows(m->d_live_cnt, d.batch * d.heads, m->Tq, m->Tk, m->d_order, m->stream));
   LA_HIP(la::launch_transpose_v(static_cast<const uint16_t*>(v), m->d_vt, d.stride_b, d.stride_h, d.stride_n,
                                 d.batch * d.heads, d.heads, d.seqlen, m->Tk, m->stream));
@@ -253,8 +253,9 @@ int lite_attn_mask_import(lite_attn_mask_t* m, const uint64_t* host_bits, size_t
 
 int lite_attn_skipruns_export(lite_attn_mask_t* m, uint32_t* host_runs, uint32_t* host_nruns) {
   if (!m || !host_runs || !host_nruns) return LITE_ATTN_EINVAL;
-  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tk, m->W, m->run_stride, m->d_runs, m->d_nruns, m->d_live_cnt,
-                            nullptr, nullptr, m->stream));
+  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tq, m->Tk, m->W,
+                            m->desc.flags & LITE_ATTN_ORDER_DIAGONAL_FIRST, m->run_stride, m->d_runs, m->d_nruns,
+                            m->d_live_cnt, nullptr, nullptr, m->stream));
   LA_HIP(hipMemcpyAsync(host_runs, m->d_runs, sizeof(uint32_t) * (size_t)m->rows * m->run_stride,
                         hipMemcpyDeviceToHost, m->stream));
   LA_HIP(hipMemcpyAsync(host_nruns, m->d_nruns, sizeof(uint32_t) * (size_t)m->rows, hipMemcpyDeviceToHost, m->stream));

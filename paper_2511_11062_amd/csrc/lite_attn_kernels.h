@@ -29,8 +29,8 @@ struct FwdParams {
 int fwd_lds_bytes();
 hipError_t prepare_fwd();
 hipError_t launch_clear(uint64_t* bits, size_t words, unsigned long long* stats, size_t nstats, hipStream_t st);
-hipError_t launch_compact(const uint64_t* bits, int rows, int Tk, int W, int run_stride, uint32_t* runs,
-                          uint32_t* nruns, uint32_t* live_cnt, unsigned long long* stat_skipped_in,
+hipError_t launch_compact(const uint64_t* bits, int rows, int Tq, int Tk, int W, int diagonal_first, int run_stride,
+                          uint32_t* runs, uint32_t* nruns, uint32_t* live_cnt, unsigned long long* stat_skipped_in,
                           unsigned long long* stat_runs, hipStream_t st);
 hipError_t launch_transpose_v(const uint16_t* v, uint16_t* vt, int64_t stride_b, int64_t stride_h, int64_t stride_n,
                               int BH, int H, int N, int Tk, hipStream_t st);

@@ -56,13 +56,15 @@ __global__ void clear_state_kernel(uint64_t* bits, size_t words, unsigned long l
 }
 
 // Skip-List compaction, one wave per Q-tile row.  The list is run-length encoded as the paper describes: one entry
-// (start | end << 16) per maximal run of consecutive live K/V tiles [start, end).  Lane l looks at bit l of each
+// (start | end << 16) per maximal run of consecutive live K/V tiles [start, end), in visiting order (ascending, or
+// -- "diagonal first" -- the tiles from the diagonal one to the last, then those before the diagonal).  Lane l looks at bit l of each
 // 64-tile word: a live tile whose predecessor is not live starts a run, one whose successor is not live ends it;
 // the k-th start and the k-th end of a row belong to the same run, so the two 16-bit halves are written
 // independently at the position given by a ballot + prefix popcount.
-__global__ __launch_bounds__(256) void compact_skiplist(const uint64_t* __restrict__ bits, int rows, int Tk, int W,
-                                                         int run_stride, uint32_t* __restrict__ runs,
-                                                         uint32_t* __restrict__ nruns, uint32_t* __restrict__ live_cnt,
+__global__ __launch_bounds__(256) void compact_skiplist(const uint64_t* __restrict__ bits, int rows, int Tq, int Tk,
+                                                         int W, int diagonal_first, int run_stride,
+                                                         uint32_t* __restrict__ runs, uint32_t* __restrict__ nruns,
+                                                         uint32_t* __restrict__ live_cnt,
                                                          unsigned long long* __restrict__ stat_skipped_in,
                                                          unsigned long long* __restrict__ stat_runs) {
   const int lane = threadIdx.x & 63;
@@ -70,26 +72,39 @@ __global__ __launch_bounds__(256) void compact_skiplist(const uint64_t* __restri
   if (row >= rows) return;
   const uint64_t* mrow = bits + (size_t)row * W;
   uint16_t* out = reinterpret_cast<uint16_t*>(runs + (size_t)row * run_stride);
-  auto live_word = [&](int w) -> uint64_t {  // bit l set = tile 64w+l exists and is not skipped
-    if (w < 0 || w >= W) return 0ull;
-    const int valid = Tk - 64 * w;
-    return ~mrow[w] & (valid >= 64 ? ~0ull : ((1ull << valid) - 1ull));
-  };
   uint32_t ns = 0, ne = 0, n = 0;
-  uint64_t prev = 0ull, cur = live_word(0);
-  for (int w = 0; w < W; ++w) {
-    const uint64_t next = live_word(w + 1);
-    const uint64_t starts = cur & ~((cur << 1) | (prev >> 63));
-    const uint64_t ends = cur & ~((cur >> 1) | (next << 63));
-    const uint64_t below = (1ull << lane) - 1ull;
-    const int j = 64 * w + lane;
-    if ((starts >> lane) & 1ull) out[2 * (ns + __popcll(starts & below))] = (uint16_t)j;
-    if ((ends >> lane) & 1ull) out[2 * (ne + __popcll(ends & below)) + 1] = (uint16_t)(j + 1);
-    ns += __popcll(starts);
-    ne += __popcll(ends);
-    n += __popcll(cur);
-    prev = cur;
-    cur = next;
+  // runs of the live tiles inside [lo, hi), ascending, appended to the list
+  auto emit = [&](int lo, int hi) {
+    auto live_word = [&](int w) -> uint64_t {  // bit l set = tile 64w+l lies in [lo, hi) and is not skipped
+      if (w < 0 || w >= W || 64 * w >= hi || 64 * w + 64 <= lo) return 0ull;
+      uint64_t m = ~mrow[w];
+      if (hi - 64 * w < 64) m &= (1ull << (hi - 64 * w)) - 1ull;
+      if (lo > 64 * w) m &= ~((1ull << (lo - 64 * w)) - 1ull);
+      return m;
+    };
+    if (hi <= lo) return;
+    uint64_t prev = 0ull, cur = live_word(lo >> 6);
+    for (int w = lo >> 6; 64 * w < hi; ++w) {
+      const uint64_t next = live_word(w + 1);
+      const uint64_t starts = cur & ~((cur << 1) | (prev >> 63));
+      const uint64_t ends = cur & ~((cur >> 1) | (next << 63));
+      const uint64_t below = (1ull << lane) - 1ull;
+      const int j = 64 * w + lane;
+      if ((starts >> lane) & 1ull) out[2 * (ns + __popcll(starts & below))] = (uint16_t)j;
+      if ((ends >> lane) & 1ull) out[2 * (ne + __popcll(ends & below)) + 1] = (uint16_t)(j + 1);
+      ns += __popcll(starts);
+      ne += __popcll(ends);
+      n += __popcll(cur);
+      prev = cur;
+      cur = next;
+    }
+  };
+  if (diagonal_first) {  // visiting order i, i+1, ..., Tk-1, 0, ..., i-1: the diagonal tile comes first
+    const int i = min(row % Tq, Tk);
+    emit(i, Tk);
+    emit(0, i);
+  } else {
+    emit(0, Tk);
   }
   if (lane == 0) {
     nruns[row] = ns;
@@ -544,9 +559,7 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
     int j_cur = c_j;
     advance();
     int j_nxt = c_j;
-    // the last live tile needs column masking if it is the ragged last tile of the sequence
-    const bool tail = (N & (kTile - 1)) != 0 && (int)(runs[nruns - 1] >> 16) == p.Tk;
-    const int n_main = tail ? cnt - 1 : cnt;
+    const bool ragged = (N & (kTile - 1)) != 0;  // the last tile of the sequence needs its columns masked
 
     // prologue: the odd V^T buffer is read (times P~ = 0) before it is first filled: make it finite; K of
     // stages 0 and 1; then S^T(0)
@@ -574,21 +587,20 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
         }
       }
     };
-    for (int t = 0; t < n_main; ++t) {
+    for (int t = 0; t < cnt; ++t) {
       advance();
       const int j_nn = c_j;  // needed one tile from now
       int* fs = (t & 1) ? flag_slot1 : flag_slot0;
-      stage<QB, 0, false>(st, ln, smem, j_cur, j_nxt, fs);
-      stage<QB, 1, false>(st, ln, smem, j_cur, j_nxt, fs);
+      if (ragged && j_cur == p.Tk - 1) {
+        stage<QB, 0, true>(st, ln, smem, j_cur, j_nxt, fs);
+        stage<QB, 1, true>(st, ln, smem, j_cur, j_nxt, fs);
+      } else {
+        stage<QB, 0, false>(st, ln, smem, j_cur, j_nxt, fs);
+        stage<QB, 1, false>(st, ln, smem, j_cur, j_nxt, fs);
+      }
       finish_tile(t, j_cur);
       j_cur = j_nxt;
       j_nxt = j_nn;
-    }
-    if (tail) {
-      int* fs = (n_main & 1) ? flag_slot1 : flag_slot0;
-      stage<QB, 0, true>(st, ln, smem, j_cur, j_cur, fs);
-      stage<QB, 1, true>(st, ln, smem, j_cur, j_cur, fs);
-      finish_tile(n_main, j_cur);
     }
     // drain: O^T += V^T P~^T of the last stage (odd parity buffer)
     mma_pv<QB>(st.oacc, st.pw, smem + kVOff + kStageBytes, ln.vread);
@@ -668,11 +680,11 @@ hipError_t launch_clear(uint64_t* bits, size_t words, unsigned long long* stats,
   return hipGetLastError();
 }
 
-hipError_t launch_compact(const uint64_t* bits, int rows, int Tk, int W, int run_stride, uint32_t* runs,
-                          uint32_t* nruns, uint32_t* live_cnt, unsigned long long* stat_skipped_in,
+hipError_t launch_compact(const uint64_t* bits, int rows, int Tq, int Tk, int W, int diagonal_first, int run_stride,
+                          uint32_t* runs, uint32_t* nruns, uint32_t* live_cnt, unsigned long long* stat_skipped_in,
                           unsigned long long* stat_runs, hipStream_t st) {
-  hipLaunchKernelGGL(compact_skiplist, dim3((rows + 3) / 4), dim3(256), 0, st, bits, rows, Tk, W, run_stride, runs,
-                     nruns, live_cnt, stat_skipped_in, stat_runs);
+  hipLaunchKernelGGL(compact_skiplist, dim3((rows + 3) / 4), dim3(256), 0, st, bits, rows, Tq, Tk, W, diagonal_first,
+                     run_stride, runs, nruns, live_cnt, stat_skipped_in, stat_runs);
   return hipGetLastError();
 }
 

@@ -57,7 +57,7 @@ def check_step(o_gpu, o_ref, m_gpu, m_ref, g_ref, thr):
 
 
 def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sample_rows=None, gen_device=None,
-                       verbose=False, seed=0, layout="bhnd"):
+                       verbose=False, seed=0, layout="bhnd", diagonal_first=False):
     """Runs `steps` denoising steps of a named workload on cuda:0 through the C ABI and checks every step.
 
     sample_rows: None = all rows; an int = that many seeded random rows plus first/last (and protected) rows.
@@ -83,7 +83,12 @@ def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sa
 
     seq = inputs.DriftSequence(wl, gen_device or ("cpu" if B * H * N <= 1 << 16 else dev))
     strides = None if layout == "bhnd" else (N * H * d, d, H * d)       # "bnhd": memory order [B,N,H,d]
-    handle = la.lite_attn_init_mask(B, H, N, protect=wl.protect, max_steps=max(steps, 1), strides=strides)
+    handle = la.lite_attn_init_mask(B, H, N, protect=wl.protect, max_steps=max(steps, 1), strides=strides,
+                                    flags=1 if diagonal_first else 0)
+    visit = None
+    if diagonal_first:
+        from oracle.lite_attn_oracle import diagonal_first as diag
+        visit = diag(Tq, Tk)
     la.lite_attn_set_stream(handle, torch.cuda.current_stream().cuda_stream)
     m_ref = np.zeros((1, len(heads), Tq, Tk), dtype=np.uint8)      # oracle mask of the compared heads
     reports = []
@@ -107,7 +112,7 @@ def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sa
             la.lite_attn_fwd(mem[0].data_ptr(), mem[1].data_ptr(), mem[2].data_ptr(), out_mem.data_ptr(), handle,
                              thr, t)
             torch.cuda.synchronize()
-            o_ref, m_new, g = oracle_step(qs, ks, vs, m_ref, thr, protect=wl.protect, rows=sub_rows)
+            o_ref, m_new, g = oracle_step(qs, ks, vs, m_ref, thr, protect=wl.protect, rows=sub_rows, visit=visit)
             o_gpu = out.reshape(B * H, N, d)[heads].float().cpu().numpy()
             m_gpu = unpack_mask(la.lite_attn_mask_export(handle).reshape(B * H * Tq, W), Tk)[rows]
             sel_o = np.zeros((len(heads), N), dtype=bool)

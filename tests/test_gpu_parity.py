@@ -45,6 +45,17 @@ def test_ragged_multi_step_with_skips():
     assert reps[-1]["skipped_out"] > 0.05
 
 
+def test_diagonal_first_order():
+    """Other j order (flag LITE_ATTN_ORDER_DIAGONAL_FIRST): parity with the oracle run on the same visiting order,
+    on a ragged shape (the tail tile is then visited in the middle of the list) and on the tiny config; and it
+    marks more tiles than the linear order at the same threshold."""
+    wl = small("ragged_diag", 2, (2, 24, 31), 3)
+    parity.run_sequence_check(wl, steps=3, thresholds=[-3.0, -2.0, -1.5], diagonal_first=True, verbose=True)
+    diag = parity.run_sequence_check("tiny", steps=3, threshold=-2.0, diagonal_first=True, verbose=True)
+    lin = parity.run_sequence_check("tiny", steps=3, threshold=-2.0)
+    assert diag[-1]["skipped_out"] > lin[-1]["skipped_out"]
+
+
 def test_protected_text_tokens_are_never_skipped():
     """Video grid of 1100 tokens + 150 text tokens (range 1100..1249 straddles tiles 8 and 9)."""
     wl = small("text", 2, (2, 22, 25), 3, text=150)
@@ -78,6 +89,32 @@ def test_skiplist_compaction_matches_host_reference():
                     assert np.array_equal(runs[r, :nruns[r]] >> 16, ends)
         finally:
             la.lite_attn_free_mask(h)
+
+
+def test_skiplist_compaction_diagonal_first_order():
+    from paper_2511_11062_amd import lite_attn as la
+    rng = np.random.default_rng(4)
+    B, H, N = 1, 2, 128 * 150 + 7
+    Tq = Tk = -(-N // 128)
+    h = la.lite_attn_init_mask(B, H, N, flags=1)
+    try:
+        for density in (0.0, 0.4, 0.95):
+            mask = (rng.random((B * H * Tq, Tk)) < density).astype(np.uint8)
+            la.lite_attn_mask_import(h, parity.pack_mask(mask), 1)
+            idx, cnt = la.lite_attn_skiplist_export(h, B * H * Tq, Tk)
+            runs, nruns = la.lite_attn_skipruns_export(h, B * H * Tq)
+            for r in range(B * H * Tq):
+                i = r % Tq
+                live = np.flatnonzero(mask[r] == 0)
+                expect = np.concatenate((live[live >= i], live[live < i]))
+                assert cnt[r] == len(expect) and np.array_equal(idx[r, :cnt[r]], expect)
+                # runs never cross the wrap-around point and are maximal inside each of the two segments
+                starts, ends = runs[r, :nruns[r]] & 0xffff, runs[r, :nruns[r]] >> 16
+                assert (ends > starts).all() and int((ends - starts).sum()) == len(expect)
+                brk = np.flatnonzero(np.diff(expect) != 1) + 1
+                assert nruns[r] == (len(brk) + 1 if len(expect) else 0)
+    finally:
+        la.lite_attn_free_mask(h)
 
 
 def test_step_protocol_and_argument_errors():
