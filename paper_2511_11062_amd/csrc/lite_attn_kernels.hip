@@ -242,19 +242,38 @@ __device__ __forceinline__ u32x4 make_rsrc(const void* ptr, uint32_t bytes) {
 // One 1 KB piece global -> LDS without registers: lane l's 16 bytes land at lds_addr + 16*l.  Written as inline
 // assembly so that the compiler does not order later LDS reads of OTHER buffers behind this load (it would wait
 // for vmcnt(0) before every LDS read); completion is enforced by the s_waitcnt vmcnt(0) + barrier ending a stage.
-__device__ __forceinline__ void dma16(const u32x4 rsrc, uint32_t lds_addr, uint32_t voffset) {
-  asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
+// LDS address = lds_base (a wave-uniform register) + kLdsOff (a compile-time constant added on the scalar unit, so
+// that the sixteen destinations of a stage pair do not each occupy a scalar register across the main loop).
+template <int kLdsOff>
+__device__ __forceinline__ void dma16(const u32x4 rsrc, uint32_t lds_base, uint32_t voffset) {
+  asm volatile("s_add_u32 m0, %2, %3\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
                :
-               : "v"(voffset), "s"(rsrc), "s"(lds_addr)
-               : "memory", "m0");
+               : "v"(voffset), "s"(rsrc), "s"(lds_base), "n"(kLdsOff)
+               : "memory", "m0", "scc");
 }
 
-template <int QB>
+template <int QB, int kBufOff, int X = 0>
 __device__ __forceinline__ void dma_stage(const u32x4 rsrc, const uint32_t* off, uint32_t stage_byte_base,
                                           uint32_t lds_wave_addr) {
-#pragma unroll
-  for (int x = 0; x < Geo<QB>::kChunks; ++x) {
-    dma16(rsrc, lds_wave_addr + 1024 * x, off[x] + stage_byte_base);
+  if constexpr (X < Geo<QB>::kChunks) {
+    dma16<kBufOff + 1024 * X>(rsrc, lds_wave_addr, off[X] + stage_byte_base);
+    dma_stage<QB, kBufOff, X + 1>(rsrc, off, stage_byte_base, lds_wave_addr);
+  }
+}
+
+// Piece x (compile-time after unrolling) of a stage: dispatch to the instance with that LDS offset.
+template <int QB, int kBufOff>
+__device__ __forceinline__ void dma_piece(int x, const u32x4 rsrc, const uint32_t* off, uint32_t stage_byte_base,
+                                          uint32_t lds_wave_addr) {
+  switch (x) {
+    case 0: dma16<kBufOff + 0 * 1024>(rsrc, lds_wave_addr, off[0] + stage_byte_base); break;
+    case 1: dma16<kBufOff + 1 * 1024>(rsrc, lds_wave_addr, off[1] + stage_byte_base); break;
+    case 2: dma16<kBufOff + 2 * 1024>(rsrc, lds_wave_addr, off[2] + stage_byte_base); break;
+    case 3: dma16<kBufOff + 3 * 1024>(rsrc, lds_wave_addr, off[3] + stage_byte_base); break;
+    case 4: dma16<kBufOff + 4 * 1024>(rsrc, lds_wave_addr, off[4 % Geo<QB>::kChunks] + stage_byte_base); break;
+    case 5: dma16<kBufOff + 5 * 1024>(rsrc, lds_wave_addr, off[5 % Geo<QB>::kChunks] + stage_byte_base); break;
+    case 6: dma16<kBufOff + 6 * 1024>(rsrc, lds_wave_addr, off[6 % Geo<QB>::kChunks] + stage_byte_base); break;
+    default: dma16<kBufOff + 7 * 1024>(rsrc, lds_wave_addr, off[7 % Geo<QB>::kChunks] + stage_byte_base); break;
   }
 }
 
@@ -311,17 +330,17 @@ constexpr int kChunkRows = 64;  // rows of one head that an XCD runs side by sid
 constexpr int kPrefetch = 3;  // LDS fragments in flight ahead of the MFMA that consumes them
 constexpr int kDmaGap = 2;    // steps between two DMA issues of a stage
 
-// One pipeline stage (64 K/V columns).  H = stage parity (half of the mask tile), TAIL = the tile may contain
-// columns past the end of the sequence.
+// One pipeline stage (64 K/V columns).  H = stage parity (half of the mask tile); is_tail (wave-uniform) = the tile
+// is the ragged last tile of the sequence, whose columns past the end must be masked.
 //
 // The stage is written as 32 steps.  Step k issues the MFMA(s) of fragment k -- first the 16 of
 // O^T += V^T(s-1) P~^T(s-1), then the 16 of S^T(s+1) -- and one slice of the online softmax of stage s (vector
 // ALU), with scheduling fences between steps so that the compiler keeps this interleaving: the matrix cores and
 // the vector ALU of the SIMD then work at the same time inside one wave.  P~ of stage s is written over P~ of
 // stage s-1 word by word, each word after the last MFMA that reads it has been issued.
-template <int QB, int H, bool TAIL>
+template <int QB, int H>
 __device__ __forceinline__ void stage(State<QB>& st, const Lane<QB>& ln, char* smem, int j_cur, int j_nxt,
-                                      int* flag_slot) {
+                                      int* flag_slot, bool is_tail) {
   f32x16(&cur)[QB][2] = H ? st.sB : st.sA;
   f32x16(&nxt)[QB][2] = H ? st.sA : st.sB;
 
@@ -368,9 +387,9 @@ __device__ __forceinline__ void stage(State<QB>& st, const Lane<QB>& ln, char* s
     if (k % kDmaGap == 0 && k / kDmaGap < 2 * kC) {
       const int x = k / kDmaGap;
       if (x < kC)
-        dma16(ln.vrsrc, ln.lds_wave + kVOff + H * kStageBytes + 1024 * x, ln.vdma[x] + vbase);
+        dma_piece<QB, kVOff + H * kStageBytes>(x, ln.vrsrc, ln.vdma, vbase, ln.lds_wave);
       else
-        dma16(ln.krsrc, ln.lds_wave + kKOff + H * kStageBytes + 1024 * (x - kC), ln.kdma[x - kC] + kbase);
+        dma_piece<QB, kKOff + H * kStageBytes>(x - kC, ln.krsrc, ln.kdma, kbase, ln.lds_wave);
     }
 
     // ---- vector ALU: slice k of the online softmax of stage s (raw dot products; 1/sqrt(d) folded into c) ----
@@ -378,13 +397,15 @@ __device__ __forceinline__ void stage(State<QB>& st, const Lane<QB>& ln, char* s
     for (int qb = 0; qb < QB; ++qb) {
       if (k < 4) {  // m_local: partial row maxima over 8 of this lane's 32 scores
         const int blk = k >> 1, r0 = 8 * (k & 1);
-        if (TAIL) {
-          const int kv0 = j_cur * kTile + H * kSub;
+        if (is_tail) {  // uniform branch, taken for one tile per row at most
+          // this lane's element r of block blk is column 32*blk + 8*(r>>2) + (r&3) + 4*hi of the stage: compare the
+          // lane-independent part with one per-lane limit (nothing here can be hoisted into 32 live registers)
+          int lim = ln.N - (j_cur * kTile + H * kSub) - 4 * ln.hi;
+          asm volatile("" : "+v"(lim));  // keeps the 8 compares below inside this branch (else all 32 lane masks of
+                                         // a stage are formed ahead of time and held in scalar registers)
 #pragma unroll
-          for (int r = r0; r < r0 + 8; ++r) {
-            const int col = kv0 + 32 * blk + 8 * (r >> 2) + 4 * ln.hi + (r & 3);
-            if (col >= ln.N) cur[qb][blk][r] = -INFINITY;
-          }
+          for (int r = r0; r < r0 + 8; ++r)
+            if (32 * blk + 8 * (r >> 2) + (r & 3) >= lim) cur[qb][blk][r] = -INFINITY;
         }
         float v = cur[qb][blk][r0];
 #pragma unroll
@@ -565,9 +586,8 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
     // stages 0 and 1; then S^T(0)
     for (int x = tid; x < kStageBytes / 16; x += kThreads)
       *reinterpret_cast<uint4*>(smem + kVOff + kStageBytes + 16 * x) = uint4{0u, 0u, 0u, 0u};
-    dma_stage<QB>(ln.krsrc, ln.kdma, (uint32_t)(j_cur * kTile) * ln.stride2, ln.lds_wave + kKOff);
-    dma_stage<QB>(ln.krsrc, ln.kdma, (uint32_t)(j_cur * kTile + kSub) * ln.stride2,
-                  ln.lds_wave + kKOff + kStageBytes);
+    dma_stage<QB, kKOff>(ln.krsrc, ln.kdma, (uint32_t)(j_cur * kTile) * ln.stride2, ln.lds_wave);
+    dma_stage<QB, kKOff + kStageBytes>(ln.krsrc, ln.kdma, (uint32_t)(j_cur * kTile + kSub) * ln.stride2, ln.lds_wave);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     mma_qk<QB>(st.sA, st.qf, smem + kKOff, ln.kread);
@@ -591,13 +611,9 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
       advance();
       const int j_nn = c_j;  // needed one tile from now
       int* fs = (t & 1) ? flag_slot1 : flag_slot0;
-      if (ragged && j_cur == p.Tk - 1) {
-        stage<QB, 0, true>(st, ln, smem, j_cur, j_nxt, fs);
-        stage<QB, 1, true>(st, ln, smem, j_cur, j_nxt, fs);
-      } else {
-        stage<QB, 0, false>(st, ln, smem, j_cur, j_nxt, fs);
-        stage<QB, 1, false>(st, ln, smem, j_cur, j_nxt, fs);
-      }
+      const bool is_tail = ragged && j_cur == p.Tk - 1;
+      stage<QB, 0>(st, ln, smem, j_cur, j_nxt, fs, is_tail);
+      stage<QB, 1>(st, ln, smem, j_cur, j_nxt, fs, is_tail);
       finish_tile(t, j_cur);
       j_cur = j_nxt;
       j_nxt = j_nn;
