@@ -48,6 +48,8 @@ constexpr int kFlagsOff = 4 * kStageBytes;  // 8 ints [tile parity][wave] + 64 d
 constexpr int kLdsBytes = kFlagsOff + 8 * 4 + 64 * 4;
 constexpr int kORow = 272;        // bytes per O row in the epilogue staging (reuses the stage buffers)
 
+constexpr int kRowsPerWave = 8;  // Q-tile rows compacted by one wave of compact_skiplist
+
 __global__ void clear_state_kernel(uint64_t* bits, size_t words, unsigned long long* stats, size_t nstats) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -55,7 +57,7 @@ __global__ void clear_state_kernel(uint64_t* bits, size_t words, unsigned long l
   for (size_t x = i; x < nstats; x += stride) stats[x] = 0;
 }
 
-// Skip-List compaction, one wave per Q-tile row.  The list is run-length encoded as the paper describes: one entry
+// Skip-List compaction, one wave per Q-tile row (a wave takes kRowsPerWave consecutive rows).  The list is run-length encoded as the paper describes: one entry
 // (start | end << 16) per maximal run of consecutive live K/V tiles [start, end), in visiting order (ascending, or
 // -- "diagonal first" -- the tiles from the diagonal one to the last, then those before the diagonal).  Lane l looks at bit l of each
 // 64-tile word: a live tile whose predecessor is not live starts a run, one whose successor is not live ends it;
@@ -68,49 +70,55 @@ __global__ __launch_bounds__(256) void compact_skiplist(const uint64_t* __restri
                                                          unsigned long long* __restrict__ stat_skipped_in,
                                                          unsigned long long* __restrict__ stat_runs) {
   const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
-  const uint64_t* mrow = bits + (size_t)row * W;
-  uint16_t* out = reinterpret_cast<uint16_t*>(runs + (size_t)row * run_stride);
-  uint32_t ns = 0, ne = 0, n = 0;
-  // runs of the live tiles inside [lo, hi), ascending, appended to the list
-  auto emit = [&](int lo, int hi) {
-    auto live_word = [&](int w) -> uint64_t {  // bit l set = tile 64w+l lies in [lo, hi) and is not skipped
-      if (w < 0 || w >= W || 64 * w >= hi || 64 * w + 64 <= lo) return 0ull;
-      uint64_t m = ~mrow[w];
-      if (hi - 64 * w < 64) m &= (1ull << (hi - 64 * w)) - 1ull;
-      if (lo > 64 * w) m &= ~((1ull << (lo - 64 * w)) - 1ull);
-      return m;
+  const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
+  unsigned long long skipped_sum = 0, runs_sum = 0;  // one pair of atomics per wave, not per row
+  for (int row = wave * kRowsPerWave; row < min(rows, (wave + 1) * kRowsPerWave); ++row) {
+    const uint64_t* mrow = bits + (size_t)row * W;
+    uint16_t* out = reinterpret_cast<uint16_t*>(runs + (size_t)row * run_stride);
+    uint32_t ns = 0, ne = 0, n = 0;
+    // runs of the live tiles inside [lo, hi), ascending, appended to the list
+    auto emit = [&](int lo, int hi) {
+      auto live_word = [&](int w) -> uint64_t {  // bit l set = tile 64w+l lies in [lo, hi) and is not skipped
+        if (w < 0 || w >= W || 64 * w >= hi || 64 * w + 64 <= lo) return 0ull;
+        uint64_t m = ~mrow[w];
+        if (hi - 64 * w < 64) m &= (1ull << (hi - 64 * w)) - 1ull;
+        if (lo > 64 * w) m &= ~((1ull << (lo - 64 * w)) - 1ull);
+        return m;
+      };
+      if (hi <= lo) return;
+      uint64_t prev = 0ull, cur = live_word(lo >> 6);
+      for (int w = lo >> 6; 64 * w < hi; ++w) {
+        const uint64_t next = live_word(w + 1);
+        const uint64_t starts = cur & ~((cur << 1) | (prev >> 63));
+        const uint64_t ends = cur & ~((cur >> 1) | (next << 63));
+        const uint64_t below = (1ull << lane) - 1ull;
+        const int j = 64 * w + lane;
+        if ((starts >> lane) & 1ull) out[2 * (ns + __popcll(starts & below))] = (uint16_t)j;
+        if ((ends >> lane) & 1ull) out[2 * (ne + __popcll(ends & below)) + 1] = (uint16_t)(j + 1);
+        ns += __popcll(starts);
+        ne += __popcll(ends);
+        n += __popcll(cur);
+        prev = cur;
+        cur = next;
+      }
     };
-    if (hi <= lo) return;
-    uint64_t prev = 0ull, cur = live_word(lo >> 6);
-    for (int w = lo >> 6; 64 * w < hi; ++w) {
-      const uint64_t next = live_word(w + 1);
-      const uint64_t starts = cur & ~((cur << 1) | (prev >> 63));
-      const uint64_t ends = cur & ~((cur >> 1) | (next << 63));
-      const uint64_t below = (1ull << lane) - 1ull;
-      const int j = 64 * w + lane;
-      if ((starts >> lane) & 1ull) out[2 * (ns + __popcll(starts & below))] = (uint16_t)j;
-      if ((ends >> lane) & 1ull) out[2 * (ne + __popcll(ends & below)) + 1] = (uint16_t)(j + 1);
-      ns += __popcll(starts);
-      ne += __popcll(ends);
-      n += __popcll(cur);
-      prev = cur;
-      cur = next;
+    if (diagonal_first) {  // visiting order i, i+1, ..., Tk-1, 0, ..., i-1: the diagonal tile comes first
+      const int i = min(row % Tq, Tk);
+      emit(i, Tk);
+      emit(0, i);
+    } else {
+      emit(0, Tk);
     }
-  };
-  if (diagonal_first) {  // visiting order i, i+1, ..., Tk-1, 0, ..., i-1: the diagonal tile comes first
-    const int i = min(row % Tq, Tk);
-    emit(i, Tk);
-    emit(0, i);
-  } else {
-    emit(0, Tk);
+    if (lane == 0) {
+      nruns[row] = ns;
+      live_cnt[row] = n;
+    }
+    skipped_sum += (unsigned long long)(Tk - n);
+    runs_sum += ns;
   }
   if (lane == 0) {
-    nruns[row] = ns;
-    live_cnt[row] = n;
-    if (stat_skipped_in && (uint32_t)Tk > n) atomicAdd(stat_skipped_in, (unsigned long long)(Tk - n));
-    if (stat_runs && ns) atomicAdd(stat_runs, (unsigned long long)ns);
+    if (stat_skipped_in && skipped_sum) atomicAdd(stat_skipped_in, skipped_sum);
+    if (stat_runs && runs_sum) atomicAdd(stat_runs, runs_sum);
   }
 }
 
@@ -699,7 +707,8 @@ hipError_t launch_clear(uint64_t* bits, size_t words, unsigned long long* stats,
 hipError_t launch_compact(const uint64_t* bits, int rows, int Tq, int Tk, int W, int diagonal_first, int run_stride,
                           uint32_t* runs, uint32_t* nruns, uint32_t* live_cnt, unsigned long long* stat_skipped_in,
                           unsigned long long* stat_runs, hipStream_t st) {
-  hipLaunchKernelGGL(compact_skiplist, dim3((rows + 3) / 4), dim3(256), 0, st, bits, rows, Tq, Tk, W, diagonal_first,
+  hipLaunchKernelGGL(compact_skiplist, dim3((rows + 4 * kRowsPerWave - 1) / (4 * kRowsPerWave)), dim3(256), 0, st, bits,
+                     rows, Tq, Tk, W, diagonal_first,
                      run_stride, runs, nruns, live_cnt, stat_skipped_in, stat_runs);
   return hipGetLastError();
 }
