@@ -20,6 +20,15 @@ sys.path.insert(0, ROOT)
 TILE_FLOP = 4.0 * 128 * 128 * 128          # QK^T + PV of one live 128x128 tile pair, d = 128
 PEAK_BF16_TFLOPS = 2500.0                  # MI355X dense bf16 MFMA, published
 
+# HBM/fabric bytes per timed launch of lite_attn_fwd_kernel from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of
+# this file with its defaults (counters are not readable from inside the process): mean over the 8 timed launches,
+# FETCH_SIZE scaled x2 and WRITE_SIZE x1 by what a 1 GiB device copy reads on the same counters.  The summary with
+# the commands is profiles/lite_attn_fwd_wan14b.txt.  Any other workload, threshold or step count reports null.
+MEASURED_TRAFFIC = {("wan14b", -3.0, 8, 2): {"read_bytes": 83.0e9, "write_bytes": 0.79e9,
+                                             "dense_step_read_bytes": 31.7e9, "sparse_step_read_bytes": 90.3e9,
+                                             "algorithmic_min_bytes": 3.09e9,
+                                             "source": "profiles/lite_attn_fwd_wan14b.txt"}}
+
 # skip threshold (natural-log units of S) used per workload when none is given
 DEFAULT_THRESHOLD = {"tiny": -2.0, "wan1.3b_dense": -float("inf"), "wan1.3b_sweep": -3.0, "wan14b": -3.0,
                      "longvideo": -3.0}
@@ -61,8 +70,8 @@ def main():
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (heads shard across GPUs with no collective; see DESIGN.md); "
-                 "--gpus %d is not supported" % args.gpus)
+        sys.exit("bench.py: this build runs on ONE GPU (heads would shard across GPUs with no collective inside "
+                 "attention); --gpus %d is not supported" % args.gpus)
 
     import torch
     from paper_2511_11062_amd import inputs
@@ -123,6 +132,7 @@ def main():
     la.lite_attn_free_mask(handle)
 
     dense = wl.dense_flops()
+    traffic = MEASURED_TRAFFIC.get((wl.name, thr, K, W))
     achieved = live_flop / (fwd_ms_total * 1e-3) / 1e12
     result = {
         "metric": "dense-equivalent attention TFLOP/s over a denoising sequence (4*B*H*N^2*d per step / time)",
@@ -140,7 +150,8 @@ def main():
         "per_step": per_step,
         "roofline": {"bound": "mfma", "kernel": "lite_attn_fwd_kernel", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None,
+                     "traffic": traffic["read_bytes"] + traffic["write_bytes"] if traffic else None,
+                     "traffic_detail": traffic,
                      "measured_mfma_only_tflops": round(mfma_peak_measured, 1),
                      "measured_mfma_only_tflops_on_k": round(mfma_peak_k, 1),
                      "frac_of_measured_mfma_only": round(achieved / mfma_peak_measured, 4),
