@@ -47,6 +47,12 @@ typedef enum {
    "Skipping Condition": other orderings reach the global maximum faster; its experiments use the linear order).
    Default: ascending j.  LITE_ATTN_ORDER_DIAGONAL_FIRST: Q tile i visits K/V tiles i, i+1, ..., Tk-1, 0, ..., i-1. */
 #define LITE_ATTN_ORDER_DIAGONAL_FIRST 1
+/* LITE_ATTN_PV_SKIP_IMMEDIATE: the paper's Algorithm 2 taken literally -- a tile whose predicate fires is dropped in
+   the very call that marks it (its exp(S) V product and row sums are not accumulated), instead of contributing once
+   more and being skipped from the next call on (the default, which is what the paper's Implementation section
+   describes for its kernel).  The Skip-Mask after the call is the same in both modes: a fired tile cannot raise the
+   running maximum.  The output of the marking call equals attention over the tiles live AFTER the call. */
+#define LITE_ATTN_PV_SKIP_IMMEDIATE 2
 
 /* Shape of one attention layer; fixed for the life of a handle. */
 typedef struct {
@@ -56,7 +62,7 @@ typedef struct {
                                              [B,H,N,d]: (H*N*d, N*d, d);  [B,N,H,d]: (N*H*d, d, H*d) */
   int32_t protect_start, protect_len;     /* token range [start, start+len) never skipped: a tile whose Q rows or
                                              K/V columns intersect it is evaluated but never marked; len 0 = none */
-  int32_t flags;                          /* 0, or LITE_ATTN_ORDER_DIAGONAL_FIRST */
+  int32_t flags;                          /* 0, or an OR of the LITE_ATTN_* flags above */
   int32_t max_steps;                      /* capacity of the per-step statistics, >= 1 */
 } lite_attn_desc_t;
 

@@ -47,7 +47,7 @@ int check_desc(const lite_attn_desc_t* d) {
   if (!d) return LITE_ATTN_EINVAL;
   if (d->batch < 1 || d->heads < 1 || d->seqlen < 1 || d->head_dim < 1 || d->tile_q < 1 || d->tile_k < 1)
     return LITE_ATTN_EINVAL;
-  if (d->max_steps < 1 || (d->flags & ~LITE_ATTN_ORDER_DIAGONAL_FIRST) != 0) return LITE_ATTN_EINVAL;
+  if (d->max_steps < 1 || (d->flags & ~(LITE_ATTN_ORDER_DIAGONAL_FIRST | LITE_ATTN_PV_SKIP_IMMEDIATE)) != 0) return LITE_ATTN_EINVAL;
   if (d->protect_len < 0 || d->protect_start < 0 ||
       (d->protect_len > 0 && (int64_t)d->protect_start + d->protect_len > d->seqlen))
     return LITE_ATTN_EINVAL;
@@ -150,7 +150,7 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
   p.rows_total = (int)m->rows;
   p.order = m->d_order;
   if (ev) LA_HIP(hipEventRecord(ev[1], m->stream));
-  LA_HIP(la::launch_fwd(p, m->stream));
+  LA_HIP(la::launch_fwd(p, (d.flags & LITE_ATTN_PV_SKIP_IMMEDIATE) != 0, m->stream));
   if (ev) LA_HIP(hipEventRecord(ev[2], m->stream));
   m->next_step = step + 1;
   return LITE_ATTN_OK;

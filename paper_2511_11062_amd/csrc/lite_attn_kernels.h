@@ -36,6 +36,6 @@ hipError_t launch_transpose_v(const uint16_t* v, uint16_t* vt, int64_t stride_b,
                               int BH, int H, int N, int Tk, hipStream_t st);
 hipError_t launch_mfma_peak(const void* data, float* sink, int iters, int blocks, hipStream_t st);
 hipError_t launch_order_rows(const uint32_t* live_cnt, int BH, int Tq, int Tk, uint32_t* order, hipStream_t st);
-hipError_t launch_fwd(const FwdParams& p, hipStream_t st);
+hipError_t launch_fwd(const FwdParams& p, bool immediate, hipStream_t st);
 
 }  // namespace la

@@ -15,12 +15,16 @@
 //   * a 128-column mask tile is streamed as two 64-column stages.  K and V stages go global -> LDS with
 //     buffer_load ... lds (no registers, rows past the end of the sequence arrive as zeros through the buffer
 //     descriptor's range check); both are stored unpadded with an XOR swizzle applied on the global-address
-//     side.  K fragments are 16-byte LDS reads, V^T fragments are ds_read_b64_tr_b16 transposing reads.
+//     side.  V is transposed once per call into a scratch (transpose_v_kernel), so that K and V^T fragments are
+//     both plain 16-byte LDS reads.
 //   * software pipeline: in stage s the matrix cores run S(s+1) = K(s+1) Q^T and O += V(s-1) P(s-1) while the
 //     vector ALU runs the online softmax of stage s; LDS holds two K and two V stages (64 KB), one barrier per
 //     stage, two workgroups per CU.
 //   * the predicate of a tile is reduced per wave with a ballot; the four per-wave results meet through LDS
 //     at the barrier that ends the tile and one lane ORs the bit into the global mask row.
+//   * IMM variant (Algorithm 2 taken literally: a tile that fires contributes nothing in the step that marks it):
+//     O += V(s-2) P(s-2) runs two stages behind instead of one, so that the verdict on a tile is known before the
+//     first of its two PV products is issued; a fired tile's PV MFMAs and row sums are then dropped.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -231,13 +235,19 @@ struct Lane {
   int N;
 };
 
-template <int QB>
+template <int QB, bool IMM>
 struct State {
   bf16x8 qf[QB][8];
   f32x16 oacc[QB][4];
   f32x16 sA[QB][2], sB[QB][2];  // S^T of even / odd stages
   uint32_t pw[QB][16];          // P~^T of the previous stage, bf16 pairs; words 4cc..4cc+3 = B operand of chunk cc
+                                // (IMM: of the previous odd stage)
+  uint32_t pw0[QB][16];         // IMM only: P~^T of the previous even stage
   float m_run[QB], l_run[QB], mloc_tile[QB];
+  // IMM only: row sum of the tile in flight (added to l_run once the tile is known not to have fired), and the
+  // rescale factor of the previous stage, which O^T has not seen yet because its PV product runs a stage later
+  float l_pend[QB], alpha_prev[QB];
+  bool grew_prev;
 };
 
 // Buffer descriptor (V#) of a raw buffer of `bytes` bytes at `ptr`: loads at offsets >= bytes return zero.
@@ -346,24 +356,31 @@ constexpr int kDmaGap = 2;    // steps between two DMA issues of a stage
 // ALU), with scheduling fences between steps so that the compiler keeps this interleaving: the matrix cores and
 // the vector ALU of the SIMD then work at the same time inside one wave.  P~ of stage s is written over P~ of
 // stage s-1 word by word, each word after the last MFMA that reads it has been issued.
-template <int QB, int H>
-__device__ __forceinline__ void stage(State<QB>& st, const Lane<QB>& ln, char* smem, int j_cur, int j_nxt,
-                                      int* flag_slot, bool is_tail) {
+//
+// IMM: the PV product of this stage is that of stage s-2 (same parity: its P~ and V^T buffers are those of parity
+// H), issued only if pv_on (wave-uniform: the tile it belongs to did not fire); the V^T stage loaded here is that of
+// stage s-1 (tile j_v, the other half), into the buffer of the other parity.
+template <int QB, int H, bool IMM>
+__device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, char* smem, int j_cur, int j_nxt,
+                                      int* flag_slot, bool is_tail, int j_v = 0, bool pv_on = true) {
   f32x16(&cur)[QB][2] = H ? st.sB : st.sA;
   f32x16(&nxt)[QB][2] = H ? st.sA : st.sB;
+  uint32_t(&pwc)[QB][16] = (IMM && !H) ? st.pw0 : st.pw;
 
   // ---- DMA: K of stage s+2 (next tile, same half) and V of this stage go into the buffers of parity H; the
   // loads are issued one at a time between the steps below (kDmaGap steps apart) so that a full memory
   // instruction queue does not hold up the MFMAs behind it ----
   const uint32_t kbase = (uint32_t)(j_nxt * kTile + H * kSub) * ln.stride2;
-  const uint32_t vbase = (uint32_t)(j_cur * kTile + H * kSub) * 2u;
+  const uint32_t vbase = IMM ? (uint32_t)(j_v * kTile + (H ^ 1) * kSub) * 2u : (uint32_t)(j_cur * kTile + H * kSub) * 2u;
+  constexpr int kVDst = kVOff + (IMM ? (H ^ 1) : H) * kStageBytes;  // V^T buffer the DMA of this stage fills
   constexpr int kC = Geo<QB>::kChunks;
 
   const char* sK = smem + kKOff + (H ^ 1) * kStageBytes;
-  const char* sV = smem + kVOff + (H ^ 1) * kStageBytes;
+  const char* sV = smem + kVOff + (IMM ? H : (H ^ 1)) * kStageBytes;
   bf16x8 frag[kPrefetch];
 #pragma unroll
-  for (int k = 0; k < kPrefetch; ++k) frag[k] = load_frag(k, sK, sV, ln.kread, ln.vread);
+  for (int k = 0; k < kPrefetch; ++k)
+    if (!IMM || pv_on) frag[k] = load_frag(k, sK, sV, ln.kread, ln.vread);
 
   float pm[QB][4], mx[QB], m_new[QB], mc[QB], alpha[QB], lsum[QB];
   bool ok = true, grew = false;
@@ -386,16 +403,21 @@ __device__ __forceinline__ void stage(State<QB>& st, const Lane<QB>& ln, char* s
       }
     } else {
       const int cc = k >> 2, db = k & 3;
+      if (!IMM || pv_on) {
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-        st.oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_operand(&st.pw[qb][4 * cc]), st.oacc[qb][db],
-                                                                  0, 0, 0);
+        for (int qb = 0; qb < QB; ++qb)
+          st.oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_operand(&pwc[qb][4 * cc]), st.oacc[qb][db],
+                                                                    0, 0, 0);
+      }
     }
-    if (k + kPrefetch < 32) frag[k % kPrefetch] = load_frag(k + kPrefetch, sK, sV, ln.kread, ln.vread);
+    if (k + kPrefetch < 32) {
+      if (!IMM || pv_on || k + kPrefetch >= 16)
+        frag[k % kPrefetch] = load_frag(k + kPrefetch, sK, sV, ln.kread, ln.vread);
+    }
     if (k % kDmaGap == 0 && k / kDmaGap < 2 * kC) {
       const int x = k / kDmaGap;
       if (x < kC)
-        dma_piece<QB, kVOff + H * kStageBytes>(x, ln.vrsrc, ln.vdma, vbase, ln.lds_wave);
+        dma_piece<QB, kVDst>(x, ln.vrsrc, ln.vdma, vbase, ln.lds_wave);
       else
         dma_piece<QB, kKOff + H * kStageBytes>(x - kC, ln.krsrc, ln.kdma, kbase, ln.lds_wave);
     }
@@ -439,9 +461,14 @@ __device__ __forceinline__ void stage(State<QB>& st, const Lane<QB>& ln, char* s
         // an empty volatile asm pins this slice to step k: without it the compiler sinks all the exponentials
         // behind the last MFMA, where nothing overlaps them
         asm volatile("" : "+v"(w), "+v"(lsum[qb]));
-        st.pw[qb][e] = w;  // word e belongs to chunk e/4, whose last reader was the MFMA of step 4*(e/4)+3 < k
+        pwc[qb][e] = w;  // word e belongs to chunk e/4, whose last reader was the MFMA of step 4*(e/4)+3 < k
       } else if (k == 22) {
-        st.l_run[qb] = st.l_run[qb] * alpha[qb] + lsum[qb];
+        if (IMM) {
+          st.l_run[qb] *= alpha[qb];
+          st.l_pend[qb] = H ? st.l_pend[qb] * alpha[qb] + lsum[qb] : lsum[qb];
+        } else {
+          st.l_run[qb] = st.l_run[qb] * alpha[qb] + lsum[qb];
+        }
         if (H) {  // skip predicate of the whole 128-column tile, once its second half is in (eq. sparge_cond)
           const float g = (st.mloc_tile[qb] - m_new[qb]) * ln.scale;  // this row; max over rows = ballot below
           ok = ok && (!ln.qvalid[qb] || (g <= ln.thr));
@@ -451,20 +478,27 @@ __device__ __forceinline__ void stage(State<QB>& st, const Lane<QB>& ln, char* s
     if (H && k == 23) *flag_slot = __all(ok) ? 1 : 0;  // lane 0: the wave's slot; other lanes: a dummy word each
     __builtin_amdgcn_sched_barrier(0);
   }
-  // O^T of the earlier stages is rescaled after this stage's PV MFMAs (rare once the running max has settled)
-  if (__any(grew)) {
+  // O^T of the earlier stages is rescaled after this stage's PV MFMAs (rare once the running max has settled).
+  // IMM: O^T now holds the products up to stage s-2 and moves to the reference maximum of stage s-1, whose product
+  // the next stage adds; this stage's own factor waits one stage.
+  if (IMM ? st.grew_prev : (bool)__any(grew)) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) st.oacc[qb][db][r] *= alpha[qb];
+        for (int r = 0; r < 16; ++r) st.oacc[qb][db][r] *= IMM ? st.alpha_prev[qb] : alpha[qb];
+  }
+  if (IMM) {
+    st.grew_prev = __any(grew);
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) st.alpha_prev[qb] = alpha[qb];
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 }
 
-template <int QB>
+template <int QB, bool IMM>
 __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kernel(const FwdParams p) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int kWaves = Geo<QB>::kWaves, kThreads = Geo<QB>::kThreads, kChunks = Geo<QB>::kChunks;
@@ -537,9 +571,12 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
   const bool q_pinned = p.protect_len > 0 && i * kTile < p.protect_start + p.protect_len &&
                         p.protect_start < min(N, (i + 1) * kTile);
 
-  State<QB> st;
+  State<QB, IMM> st;
+  st.grew_prev = false;
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
+    st.l_pend[qb] = 0.f;
+    st.alpha_prev[qb] = 1.f;
     const int qrow = i * kTile + 32 * (QB * wave + qb) + lq;
     ln.qvalid[qb] = qrow < N;
     // Q^T fragments: B operand of S^T = K Q^T, kept for the whole row.
@@ -592,8 +629,9 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
 
     // prologue: the odd V^T buffer is read (times P~ = 0) before it is first filled: make it finite; K of
     // stages 0 and 1; then S^T(0)
-    for (int x = tid; x < kStageBytes / 16; x += kThreads)
-      *reinterpret_cast<uint4*>(smem + kVOff + kStageBytes + 16 * x) = uint4{0u, 0u, 0u, 0u};
+    if (!IMM)
+      for (int x = tid; x < kStageBytes / 16; x += kThreads)
+        *reinterpret_cast<uint4*>(smem + kVOff + kStageBytes + 16 * x) = uint4{0u, 0u, 0u, 0u};
     dma_stage<QB, kKOff>(ln.krsrc, ln.kdma, (uint32_t)(j_cur * kTile) * ln.stride2, ln.lds_wave);
     dma_stage<QB, kKOff + kStageBytes>(ln.krsrc, ln.kdma, (uint32_t)(j_cur * kTile + kSub) * ln.stride2, ln.lds_wave);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -601,6 +639,21 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
     mma_qk<QB>(st.sA, st.qf, smem + kKOff, ln.kread);
     __syncthreads();
 
+    // IMM: every wave reads the four per-wave results and the pinned-range rule itself (it needs the verdict to
+    // gate the tile's PV products); returns whether the tile fired (wave-uniform)
+    auto finish_tile_imm = [&](int t, int j) -> bool {
+      const int4 f = *reinterpret_cast<const int4*>(flags + (t & 1) * 4);
+      static_assert(!IMM || kWaves == 4, "four per-wave flags per tile");
+      const int all = __builtin_amdgcn_readfirstlane(f.x & f.y & f.z & f.w);
+      const bool k_pinned = p.protect_len > 0 && j * kTile < p.protect_start + p.protect_len &&
+                            p.protect_start < min(N, (j + 1) * kTile);
+      const bool fired = all && !q_pinned && !k_pinned;
+      if (tid == 0 && fired) {
+        atomicOr(reinterpret_cast<unsigned long long*>(p.bits + (size_t)row * p.W + (j >> 6)), 1ull << (j & 63));
+        ++newly;
+      }
+      return fired;
+    };
     auto finish_tile = [&](int t, int j) {
       // the per-wave results of the finished tile meet here; one lane updates the mask
       if (tid == 0) {
@@ -615,19 +668,50 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
         }
       }
     };
+    bool pv_on = false;  // IMM: the previous tile did not fire, its PV products are due
+    int j_prev = j_cur;
     for (int t = 0; t < cnt; ++t) {
       advance();
       const int j_nn = c_j;  // needed one tile from now
       int* fs = (t & 1) ? flag_slot1 : flag_slot0;
       const bool is_tail = ragged && j_cur == p.Tk - 1;
-      stage<QB, 0>(st, ln, smem, j_cur, j_nxt, fs, is_tail);
-      stage<QB, 1>(st, ln, smem, j_cur, j_nxt, fs, is_tail);
-      finish_tile(t, j_cur);
+      if constexpr (IMM) {
+        stage<QB, 0, true>(st, ln, smem, j_cur, j_nxt, fs, is_tail, j_prev, pv_on);
+        stage<QB, 1, true>(st, ln, smem, j_cur, j_nxt, fs, is_tail, j_cur, pv_on);
+        pv_on = !finish_tile_imm(t, j_cur);
+        if (pv_on) {
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) st.l_run[qb] += st.l_pend[qb];
+        }
+        j_prev = j_cur;
+      } else {
+        stage<QB, 0, false>(st, ln, smem, j_cur, j_nxt, fs, is_tail);
+        stage<QB, 1, false>(st, ln, smem, j_cur, j_nxt, fs, is_tail);
+        finish_tile(t, j_cur);
+      }
       j_cur = j_nxt;
       j_nxt = j_nn;
     }
-    // drain: O^T += V^T P~^T of the last stage (odd parity buffer)
-    mma_pv<QB>(st.oacc, st.pw, smem + kVOff + kStageBytes, ln.vread);
+    if constexpr (IMM) {
+      // drain: the second V^T stage of the last tile is still to be loaded; then both of its PV products, the
+      // rescale factor of its second stage in between
+      dma_stage<QB, kVOff + kStageBytes>(ln.vrsrc, ln.vdma, (uint32_t)(j_prev * kTile + kSub) * 2u, ln.lds_wave);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (pv_on) mma_pv<QB>(st.oacc, st.pw0, smem + kVOff, ln.vread);
+      if (st.grew_prev) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+          for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st.oacc[qb][db][r] *= st.alpha_prev[qb];
+      }
+      if (pv_on) mma_pv<QB>(st.oacc, st.pw, smem + kVOff + kStageBytes, ln.vread);
+    } else {
+      // drain: O^T += V^T P~^T of the last stage (odd parity buffer)
+      mma_pv<QB>(st.oacc, st.pw, smem + kVOff + kStageBytes, ln.vread);
+    }
     __syncthreads();
   }
   if (tid == 0 && newly) atomicAdd(p.stat_newly, (unsigned long long)newly);
@@ -723,7 +807,10 @@ hipError_t launch_transpose_v(const uint16_t* v, uint16_t* vt, int64_t stride_b,
 constexpr int kQB = 1;  // 32 Q rows per wave, 4 waves per workgroup, 2 workgroups per CU
 
 hipError_t prepare_fwd() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(lite_attn_fwd_kernel<kQB>),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lite_attn_fwd_kernel<kQB, false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, fwd_lds_bytes());
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(lite_attn_fwd_kernel<kQB, true>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, fwd_lds_bytes());
 }
 
@@ -733,12 +820,17 @@ hipError_t launch_order_rows(const uint32_t* live_cnt, int BH, int Tq, int Tk, u
   return hipGetLastError();
 }
 
-hipError_t launch_fwd(const FwdParams& p, hipStream_t st) {
+hipError_t launch_fwd(const FwdParams& p, bool immediate, hipStream_t st) {
   // upper bound of the number of rows an XCD owns: ceil(chunks / 8) chunks of kChunkRows rows
   const int BH = p.rows_total / p.Tq;
   const int chunks = ((p.Tq + kChunkRows - 1) / kChunkRows) * BH;
   const int per_xcd = ((chunks + 7) / 8) * kChunkRows;
-  hipLaunchKernelGGL(lite_attn_fwd_kernel<kQB>, dim3(8 * per_xcd), dim3(Geo<kQB>::kThreads), fwd_lds_bytes(), st, p);
+  if (immediate)
+    hipLaunchKernelGGL((lite_attn_fwd_kernel<kQB, true>), dim3(8 * per_xcd), dim3(Geo<kQB>::kThreads), fwd_lds_bytes(),
+                       st, p);
+  else
+    hipLaunchKernelGGL((lite_attn_fwd_kernel<kQB, false>), dim3(8 * per_xcd), dim3(Geo<kQB>::kThreads), fwd_lds_bytes(),
+                       st, p);
   return hipGetLastError();
 }
 

@@ -18,12 +18,12 @@ from . import inputs
 from . import lite_attn as la
 
 
-def run_sequence(wl, data, thresholds, dense_out=None, diagonal_first=False):
+def run_sequence(wl, data, thresholds, dense_out=None, diagonal_first=False, immediate=False):
     """thresholds: one value per step.  Returns (outputs or None, per-step dicts).  If dense_out is given, eta is
     computed against it; otherwise the outputs are returned (used to produce the dense reference)."""
     B, H, N = wl.batch, wl.heads, wl.seqlen
     steps = len(data)
-    h = la.lite_attn_init_mask(B, H, N, protect=wl.protect, max_steps=steps, flags=1 if diagonal_first else 0)
+    h = la.lite_attn_init_mask(B, H, N, protect=wl.protect, max_steps=steps, flags=(1 if diagonal_first else 0) | (2 if immediate else 0))
     la.lite_attn_set_stream(h, torch.cuda.current_stream().cuda_stream)
     la.lite_attn_profile(h, True)
     outs, rows = [], []
@@ -55,15 +55,17 @@ def main():
     ap.add_argument("--json", action="store_true", help="print one JSON document instead of a table")
     ap.add_argument("--diagonal-first", action="store_true",
                     help="visit the K/V tiles of Q tile i in the order i, i+1, ..., Tk-1, 0, ..., i-1")
+    ap.add_argument("--immediate", action="store_true",
+                    help="drop a fired tile in the call that marks it (Algorithm 2 literally) instead of from the next call on")
     args = ap.parse_args()
     wl = inputs.WORKLOADS[args.workload]
     steps = args.steps or wl.steps
     seq = inputs.DriftSequence(wl, "cuda:0")
     data = [next(seq) for _ in range(steps)]
     dense_out, dense_rows = run_sequence(wl, data, [-float("inf")] * steps)
-    result = {"workload": wl.name, "steps": steps, "diagonal_first": args.diagonal_first, "dense_ms": [r["attn_ms"] for r in dense_rows], "runs": []}
+    result = {"workload": wl.name, "steps": steps, "diagonal_first": args.diagonal_first, "immediate": args.immediate, "dense_ms": [r["attn_ms"] for r in dense_rows], "runs": []}
     for thr in args.thresholds:
-        _, rows = run_sequence(wl, data, [thr] * steps, dense_out, args.diagonal_first)
+        _, rows = run_sequence(wl, data, [thr] * steps, dense_out, args.diagonal_first, args.immediate)
         result["runs"].append({"threshold": thr, "per_step": rows})
     if args.json:
         print(json.dumps(result))

@@ -40,8 +40,12 @@ def compare_output(o_gpu: np.ndarray, o_ref: np.ndarray):
     return float(d.max()), float(d.mean()), float(np.abs(o_ref).max())
 
 
-def check_step(o_gpu, o_ref, m_gpu, m_ref, g_ref, thr):
-    """Raises AssertionError on a parity violation; returns a small report dict."""
+def check_step(o_gpu, o_ref, m_gpu, m_ref, g_ref, thr, o_keep=None):
+    """Raises AssertionError on a parity violation; returns a small report dict.  o_keep: optional boolean selector
+    of the output rows to compare (immediate mode leaves out Q tiles that have a mask bit excused by the band: there
+    the two sides may legitimately have dropped different tiles from the output)."""
+    if o_keep is not None:
+        o_gpu, o_ref = o_gpu[o_keep], o_ref[o_keep]
     mx, mean, omax = compare_output(o_gpu, o_ref)
     assert np.isfinite(o_gpu).all(), "non-finite output"
     assert mx <= MAX_REL * omax, "max|dO| = %.3e > %.1e * max|O| (%.3e)" % (mx, MAX_REL, omax)
@@ -57,10 +61,11 @@ def check_step(o_gpu, o_ref, m_gpu, m_ref, g_ref, thr):
 
 
 def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sample_rows=None, gen_device=None,
-                       verbose=False, seed=0, layout="bhnd", diagonal_first=False):
+                       verbose=False, seed=0, layout="bhnd", diagonal_first=False, immediate=False):
     """Runs `steps` denoising steps of a named workload on cuda:0 through the C ABI and checks every step.
 
     sample_rows: None = all rows; an int = that many seeded random rows plus first/last (and protected) rows.
+    immediate: both sides drop a fired tile in the call that marks it (Algorithm 2 literally).
     Returns the list of per-step reports."""
     from paper_2511_11062_amd import lite_attn as la
     wl = inputs.WORKLOADS[workload] if isinstance(workload, str) else workload
@@ -84,7 +89,7 @@ def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sa
     seq = inputs.DriftSequence(wl, gen_device or ("cpu" if B * H * N <= 1 << 16 else dev))
     strides = None if layout == "bhnd" else (N * H * d, d, H * d)       # "bnhd": memory order [B,N,H,d]
     handle = la.lite_attn_init_mask(B, H, N, protect=wl.protect, max_steps=max(steps, 1), strides=strides,
-                                    flags=1 if diagonal_first else 0)
+                                    flags=(1 if diagonal_first else 0) | (2 if immediate else 0))
     visit = None
     if diagonal_first:
         from oracle.lite_attn_oracle import diagonal_first as diag
@@ -112,14 +117,24 @@ def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sa
             la.lite_attn_fwd(mem[0].data_ptr(), mem[1].data_ptr(), mem[2].data_ptr(), out_mem.data_ptr(), handle,
                              thr, t)
             torch.cuda.synchronize()
-            o_ref, m_new, g = oracle_step(qs, ks, vs, m_ref, thr, protect=wl.protect, rows=sub_rows, visit=visit)
+            o_ref, m_new, g = oracle_step(qs, ks, vs, m_ref, thr, protect=wl.protect, rows=sub_rows, visit=visit,
+                                          immediate=immediate)
             o_gpu = out.reshape(B * H, N, d)[heads].float().cpu().numpy()
             m_gpu = unpack_mask(la.lite_attn_mask_export(handle).reshape(B * H * Tq, W), Tk)[rows]
             sel_o = np.zeros((len(heads), N), dtype=bool)
             for r in sub_rows:
                 sel_o[r // Tq, (r % Tq) * 128:min(N, (r % Tq + 1) * 128)] = True
-            rep = check_step(o_gpu[sel_o], o_ref[0][sel_o], m_gpu, m_new.reshape(-1, Tk)[sub_rows],
-                             g.reshape(-1, Tk)[sub_rows], thr)
+            g_rows = g.reshape(-1, Tk)[sub_rows]
+            o_keep = None
+            if immediate:
+                with np.errstate(invalid="ignore"):
+                    near = (np.abs(g_rows - thr) <= G_BAND).any(axis=1)        # per compared Q tile, in sub_rows order
+                keep_tile = {r: not n for r, n in zip(sub_rows, near)}
+                tile_of_token = np.zeros((len(heads), N), dtype=np.int64)
+                tile_of_token[:] = np.arange(N) // 128
+                tile_of_token += (np.arange(len(heads)) * Tq)[:, None]
+                o_keep = np.array([keep_tile[int(x)] for x in tile_of_token[sel_o]])
+            rep = check_step(o_gpu[sel_o], o_ref[0][sel_o], m_gpu, m_new.reshape(-1, Tk)[sub_rows], g_rows, thr, o_keep)
             st = la.lite_attn_skip_stats(handle, t)
             rep.update(step=t, threshold=thr, gpu_skipped_in=st.tiles_skipped_in / st.tiles_total,
                        gpu_newly=st.tiles_newly_marked / st.tiles_total)

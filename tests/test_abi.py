@@ -48,7 +48,7 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
                     args.get("tile_k", 128), strides[0], strides[1], strides[2], args.get("ps", 0), args.get("pl", 0),
                     args.get("flags", 0), args.get("max_steps", 4))
         return lib.lite_attn_init_mask(ctypes.byref(d), ctypes.byref(h))
-    assert rc(batch=0) == -1 and rc(seqlen=0) == -1 and rc(max_steps=0) == -1 and rc(flags=2) == -1
+    assert rc(batch=0) == -1 and rc(seqlen=0) == -1 and rc(max_steps=0) == -1 and rc(flags=4) == -1
     assert rc(strides=(0, 100, 128)) == -1            # stride not a multiple of 8 elements
     assert rc(strides=(65536, 0, 128)) == -1          # two heads on top of each other
     assert rc(pl=10, ps=250) == -1                    # protected range past the end

@@ -180,3 +180,30 @@ def test_threshold_schedule_driver_meets_its_error_bounds():
         # driver then marks as little as it can (the most negative threshold) and says so
         assert (s["eta"] <= s["bound"]) == s["met"]
         assert s["met"] or s["threshold"] == -12.0
+
+
+@pytest.mark.parametrize("diagonal_first", [False, True])
+def test_immediate_pv_skip_mode(diagonal_first):
+    """Flag LITE_ATTN_PV_SKIP_IMMEDIATE (Algorithm 2 literally): parity with the oracle's immediate mode -- the output
+    of the marking step already lacks the fired tiles -- on the tiny config, on a ragged shape and with protected
+    text tokens; the masks equal those of the deferred mode."""
+    imm = parity.run_sequence_check("tiny", steps=4, thresholds=[-3.5, -3.0, -2.0, -1.0], immediate=True,
+                                    diagonal_first=diagonal_first, verbose=True)
+    dfr = parity.run_sequence_check("tiny", steps=4, thresholds=[-3.5, -3.0, -2.0, -1.0], diagonal_first=diagonal_first)
+    assert [r["skipped_out"] for r in imm] == [r["skipped_out"] for r in dfr]
+    assert imm[0]["gpu_newly"] > 0.05
+    wl = small("ragged_imm", 2, (2, 24, 31), 3)
+    parity.run_sequence_check(wl, steps=3, thresholds=[-3.0, -2.0, -1.5], immediate=True,
+                              diagonal_first=diagonal_first, verbose=True)
+    wl = small("text_imm", 2, (1, 25, 44), 3, text=150)
+    parity.run_sequence_check(wl, steps=3, thresholds=[-2.5, -2.0, -1.0], immediate=True,
+                              diagonal_first=diagonal_first, verbose=True)
+
+
+@pytest.mark.parametrize("n_grid", [(1, 1, 1), (1, 5, 17), (1, 8, 16), (1, 9, 16), (3, 10, 30)])
+def test_immediate_mode_short_rows(n_grid):
+    """Rows of one and two tiles (N = 1, 85, 128, 144) go through the immediate variant's drain path alone; with the
+    threshold disabled the result is dense attention, with a threshold it still matches the oracle."""
+    wl = small("short_imm", 3, n_grid, 2, batch=2)
+    parity.run_sequence_check(wl, steps=1, threshold=NINF, immediate=True)
+    parity.run_sequence_check(wl, steps=2, thresholds=[-1.0, -0.5], immediate=True)
