@@ -224,8 +224,8 @@ template <int QB>
 struct Lane {
   u32x4 krsrc, vrsrc;  // buffer descriptors of this head's K (range-checked: rows past the end read as 0) and V^T
   uint32_t kdma[Geo<QB>::kChunks], vdma[Geo<QB>::kChunks];  // byte offsets (inside a stage) of this lane's DMA pieces
-  uint32_t kread[8];  // LDS byte offset of the K fragment for d-chunk kk (stage and block go into immediates)
-  uint32_t vread[4];  // LDS byte offset of the V^T fragment for column chunk cc (d-block via immediates)
+  uint32_t kread[8];  // LDS address of the K fragment for d-chunk kk in stage buffer 0 (stage and block: immediates)
+  uint32_t vread[4];  // LDS address of the V^T fragment for column chunk cc in buffer 0 (d-block via immediates)
   uint32_t lds_wave;  // LDS address of this wave's first DMA piece inside stage buffer 0 (wave-uniform)
   uint32_t stride2;   // stride_n * 2 (bytes per token row)
   int hi;
@@ -255,6 +255,20 @@ __device__ __forceinline__ u32x4 make_rsrc(const void* ptr, uint32_t bytes) {
   const uint64_t a = reinterpret_cast<uint64_t>(ptr);
   u32x4 r = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, bytes, 0x00020000u};
   return r;
+}
+
+// Descriptor of the same buffer seen from `off` bytes in (wave-uniform, scalar arithmetic): base += off, size -= off
+// (0 if off is past the end, so that every load through it returns zeros).  Folding the moving part of a DMA address
+// into the descriptor leaves the per-lane offsets loop-invariant: no vector add per load.
+__device__ __forceinline__ u32x4 rebase(const u32x4 r, uint32_t off) {
+  off = __builtin_amdgcn_readfirstlane(off);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(r[0]), hi = __builtin_amdgcn_readfirstlane(r[1]);
+  const uint32_t size = __builtin_amdgcn_readfirstlane(r[2]);
+  const uint64_t a = (((uint64_t)hi << 32) | lo) + off;
+  uint32_t left;  // max(size - off, 0) on the scalar unit (the compiler's saturating subtract is a vector instruction)
+  asm("s_sub_u32 %0, %1, %2\n\ts_cselect_b32 %0, 0, %0" : "=s"(left) : "s"(size), "s"(off) : "scc");
+  u32x4 o = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, left, (uint32_t)__builtin_amdgcn_readfirstlane(r[3])};
+  return o;
 }
 
 // One 1 KB piece global -> LDS without registers: lane l's 16 bytes land at lds_addr + 16*l.  Written as inline
@@ -300,9 +314,9 @@ __device__ __forceinline__ bf16x8 p_operand(const uint32_t* w) {
   return __builtin_bit_cast(bf16x8, v);
 }
 
-// S^T(next) = K Q^T for one 64-column stage held in LDS at sK.
+// S^T(next) = K Q^T for one 64-column stage held in LDS at byte offset sK (kread: absolute addresses in buffer 0).
 template <int QB>
-__device__ __forceinline__ void mma_qk(f32x16 (&nxt)[QB][2], const bf16x8 (&qf)[QB][8], const char* sK,
+__device__ __forceinline__ void mma_qk(f32x16 (&nxt)[QB][2], const bf16x8 (&qf)[QB][8], int sK,
                                        const uint32_t (&kread)[8]) {
 #pragma unroll
   for (int blk = 0; blk < 2; ++blk) {
@@ -312,7 +326,7 @@ __device__ __forceinline__ void mma_qk(f32x16 (&nxt)[QB][2], const bf16x8 (&qf)[
       for (int r = 0; r < 16; ++r) nxt[qb][blk][r] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(sK + 8192 * blk + kread[kk]);
+      const bf16x8 a = *reinterpret_cast<LA_LDS const bf16x8*>(kread[kk] + (uint32_t)(sK + 8192 * blk));
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb)
         nxt[qb][blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][kk], nxt[qb][blk], 0, 0, 0);
@@ -320,15 +334,15 @@ __device__ __forceinline__ void mma_qk(f32x16 (&nxt)[QB][2], const bf16x8 (&qf)[
   }
 }
 
-// O^T += V^T P~^T for one 64-column stage held in LDS at sV ([d][64 kv], 128-byte rows).
+// O^T += V^T P~^T for one 64-column stage held in LDS at byte offset sV ([d][64 kv], 128-byte rows).
 template <int QB>
-__device__ __forceinline__ void mma_pv(f32x16 (&oacc)[QB][4], const uint32_t (&pw)[QB][16], const char* sV,
+__device__ __forceinline__ void mma_pv(f32x16 (&oacc)[QB][4], const uint32_t (&pw)[QB][16], int sV,
                                        const uint32_t (&vread)[4]) {
 #pragma unroll
   for (int cc = 0; cc < 4; ++cc)
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(sV + 4096 * db + vread[cc]);
+      const bf16x8 a = *reinterpret_cast<LA_LDS const bf16x8*>(vread[cc] + (uint32_t)(sV + 4096 * db));
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb)
         oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_operand(&pw[qb][4 * cc]), oacc[qb][db], 0, 0, 0);
@@ -336,20 +350,23 @@ __device__ __forceinline__ void mma_pv(f32x16 (&oacc)[QB][4], const uint32_t (&p
 }
 
 // LDS -> register fragment k of a stage's matrix work: k < 16 is the V^T fragment (column chunk k/4, d-block k%4)
-// of O^T += V^T P~^T, k >= 16 the K fragment (block (k-16)/8, d-chunk (k-16)%8) of S^T(s+1) = K Q^T.
-__device__ __forceinline__ bf16x8 load_frag(int k, const char* sK, const char* sV, const uint32_t (&kread)[8],
-                                            const uint32_t (&vread)[4]) {
-  if (k >= 16) return *reinterpret_cast<const bf16x8*>(sK + 8192 * ((k - 16) >> 3) + kread[k & 7]);
+// of O^T += V^T P~^T, k >= 16 the K fragment (block k%2, d-chunk (k-16)/2) of S^T(s+1) = K Q^T: the two 32-column
+// blocks alternate, so that consecutive MFMAs never accumulate into the same registers.
+// kread / vread hold absolute LDS addresses (of stage buffer 0), kK / kV are the byte offsets of the stage buffers
+// read: every fragment address is one loop-invariant register plus an immediate.
+template <int kK, int kV>
+__device__ __forceinline__ bf16x8 load_frag(int k, const uint32_t (&kread)[8], const uint32_t (&vread)[4]) {
+  if (k >= 16) return *reinterpret_cast<LA_LDS const bf16x8*>(kread[(k - 16) >> 1] + (uint32_t)(kK + 8192 * (k & 1)));
   const int cc = k >> 2, db = k & 3;
-  return *reinterpret_cast<const bf16x8*>(sV + 4096 * db + vread[cc]);
+  return *reinterpret_cast<LA_LDS const bf16x8*>(vread[cc] + (uint32_t)(kV + 4096 * db));
 }
 
 constexpr int kChunkRows = 64;  // rows of one head that an XCD runs side by side (2 workgroups x 32 CUs)
 constexpr int kPrefetch = 3;  // LDS fragments in flight ahead of the MFMA that consumes them
 constexpr int kDmaGap = 2;    // steps between two DMA issues of a stage
 
-// One pipeline stage (64 K/V columns).  H = stage parity (half of the mask tile); is_tail (wave-uniform) = the tile
-// is the ragged last tile of the sequence, whose columns past the end must be masked.
+// One pipeline stage (64 K/V columns).  H = stage parity (half of the mask tile); j_tail = index of the ragged last
+// tile of the sequence, whose columns past the end must be masked (-1 if the sequence ends on a tile boundary).
 //
 // The stage is written as 32 steps.  Step k issues the MFMA(s) of fragment k -- first the 16 of
 // O^T += V^T(s-1) P~^T(s-1), then the 16 of S^T(s+1) -- and one slice of the online softmax of stage s (vector
@@ -362,7 +379,7 @@ constexpr int kDmaGap = 2;    // steps between two DMA issues of a stage
 // stage s-1 (tile j_v, the other half), into the buffer of the other parity.
 template <int QB, int H, bool IMM>
 __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, char* smem, int j_cur, int j_nxt,
-                                      int* flag_slot, bool is_tail, int j_v = 0, bool pv_on = true) {
+                                      int* flag_slot, int j_tail, int j_v = 0, bool pv_on = true) {
   f32x16(&cur)[QB][2] = H ? st.sB : st.sA;
   f32x16(&nxt)[QB][2] = H ? st.sA : st.sB;
   uint32_t(&pwc)[QB][16] = (IMM && !H) ? st.pw0 : st.pw;
@@ -370,17 +387,18 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
   // ---- DMA: K of stage s+2 (next tile, same half) and V of this stage go into the buffers of parity H; the
   // loads are issued one at a time between the steps below (kDmaGap steps apart) so that a full memory
   // instruction queue does not hold up the MFMAs behind it ----
-  const uint32_t kbase = (uint32_t)(j_nxt * kTile + H * kSub) * ln.stride2;
-  const uint32_t vbase = IMM ? (uint32_t)(j_v * kTile + (H ^ 1) * kSub) * 2u : (uint32_t)(j_cur * kTile + H * kSub) * 2u;
+  const u32x4 krs = rebase(ln.krsrc, (uint32_t)(j_nxt * kTile + H * kSub) * ln.stride2);
+  const u32x4 vrs =
+      rebase(ln.vrsrc, IMM ? (uint32_t)(j_v * kTile + (H ^ 1) * kSub) * 2u : (uint32_t)(j_cur * kTile + H * kSub) * 2u);
   constexpr int kVDst = kVOff + (IMM ? (H ^ 1) : H) * kStageBytes;  // V^T buffer the DMA of this stage fills
   constexpr int kC = Geo<QB>::kChunks;
 
-  const char* sK = smem + kKOff + (H ^ 1) * kStageBytes;
-  const char* sV = smem + kVOff + (IMM ? H : (H ^ 1)) * kStageBytes;
+  constexpr int kKSrc = kKOff + (H ^ 1) * kStageBytes;                // K stage read by S^T(s+1)
+  constexpr int kVSrc = kVOff + (IMM ? H : (H ^ 1)) * kStageBytes;    // V^T stage read by the PV product
   bf16x8 frag[kPrefetch];
 #pragma unroll
   for (int k = 0; k < kPrefetch; ++k)
-    if (!IMM || pv_on) frag[k] = load_frag(k, sK, sV, ln.kread, ln.vread);
+    if (!IMM || pv_on) frag[k] = load_frag<kKSrc, kVSrc>(k, ln.kread, ln.vread);
 
   float pm[QB][4], mx[QB], m_new[QB], mc[QB], alpha[QB], lsum[QB];
   bool ok = true, grew = false;
@@ -391,7 +409,7 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
     // ---- matrix cores ----
     const bf16x8 a = frag[k % kPrefetch];
     if (k >= 16) {
-      const int blk = (k - 16) >> 3, kk = k & 7;
+      const int blk = k & 1, kk = (k - 16) >> 1;
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         if (kk == 0) {
@@ -412,14 +430,14 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
     }
     if (k + kPrefetch < 32) {
       if (!IMM || pv_on || k + kPrefetch >= 16)
-        frag[k % kPrefetch] = load_frag(k + kPrefetch, sK, sV, ln.kread, ln.vread);
+        frag[k % kPrefetch] = load_frag<kKSrc, kVSrc>(k + kPrefetch, ln.kread, ln.vread);
     }
     if (k % kDmaGap == 0 && k / kDmaGap < 2 * kC) {
       const int x = k / kDmaGap;
       if (x < kC)
-        dma_piece<QB, kVDst>(x, ln.vrsrc, ln.vdma, vbase, ln.lds_wave);
+        dma_piece<QB, kVDst>(x, vrs, ln.vdma, 0u, ln.lds_wave);
       else
-        dma_piece<QB, kKOff + H * kStageBytes>(x - kC, ln.krsrc, ln.kdma, kbase, ln.lds_wave);
+        dma_piece<QB, kKOff + H * kStageBytes>(x - kC, krs, ln.kdma, 0u, ln.lds_wave);
     }
 
     // ---- vector ALU: slice k of the online softmax of stage s (raw dot products; 1/sqrt(d) folded into c) ----
@@ -427,7 +445,9 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
     for (int qb = 0; qb < QB; ++qb) {
       if (k < 4) {  // m_local: partial row maxima over 8 of this lane's 32 scores
         const int blk = k >> 1, r0 = 8 * (k & 1);
-        if (is_tail) {  // uniform branch, taken for one tile per row at most
+        int jt = j_tail;
+        asm volatile("" : "+s"(jt));  // a fresh scalar compare per step (a shared one becomes a lane mask + vector ops)
+        if (j_cur == jt) {  // scalar compare and branch, taken for one tile per row at most
           // this lane's element r of block blk is column 32*blk + 8*(r>>2) + (r&3) + 4*hi of the stage: compare the
           // lane-independent part with one per-lane limit (nothing here can be hoisted into 32 live registers)
           int lim = ln.N - (j_cur * kTile + H * kSub) - 4 * ln.hi;
@@ -564,10 +584,11 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
     const int rv = 8 * (kChunks * wave + x) + (lane >> 3), pv = lane & 7;
     ln.vdma[x] = (uint32_t)rv * vt_row_bytes + 16 * (pv ^ ((rv >> 1) & 7));
   }
+  const uint32_t lds0 = (uint32_t)(size_t)(LA_LDS char*)smem;
 #pragma unroll
-  for (int kk = 0; kk < 8; ++kk) ln.kread[kk] = lq * 256 + ((32 * kk) ^ (16 * (ln.hi ^ (lq & 15))));
+  for (int kk = 0; kk < 8; ++kk) ln.kread[kk] = lds0 + lq * 256 + ((32 * kk) ^ (16 * (ln.hi ^ (lq & 15))));
 #pragma unroll
-  for (int cc = 0; cc < 4; ++cc) ln.vread[cc] = lq * 128 + ((32 * cc + 16 * ln.hi) ^ (16 * ((lq >> 1) & 7)));
+  for (int cc = 0; cc < 4; ++cc) ln.vread[cc] = lds0 + lq * 128 + ((32 * cc + 16 * ln.hi) ^ (16 * ((lq >> 1) & 7)));
   const bool q_pinned = p.protect_len > 0 && i * kTile < p.protect_start + p.protect_len &&
                         p.protect_start < min(N, (i + 1) * kTile);
 
@@ -625,7 +646,9 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
     int j_cur = c_j;
     advance();
     int j_nxt = c_j;
-    const bool ragged = (N & (kTile - 1)) != 0;  // the last tile of the sequence needs its columns masked
+    // the last tile of a sequence that ends inside it needs its columns masked; the stages compare their tile index
+    // with this one on the scalar unit (a bool would travel between their blocks as a lane mask)
+    const int j_tail = (N & (kTile - 1)) != 0 ? p.Tk - 1 : -1;
 
     // prologue: the odd V^T buffer is read (times P~ = 0) before it is first filled: make it finite; K of
     // stages 0 and 1; then S^T(0)
@@ -636,7 +659,7 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
     dma_stage<QB, kKOff + kStageBytes>(ln.krsrc, ln.kdma, (uint32_t)(j_cur * kTile + kSub) * ln.stride2, ln.lds_wave);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    mma_qk<QB>(st.sA, st.qf, smem + kKOff, ln.kread);
+    mma_qk<QB>(st.sA, st.qf, kKOff, ln.kread);
     __syncthreads();
 
     // IMM: every wave reads the four per-wave results and the pinned-range rule itself (it needs the verdict to
@@ -674,10 +697,9 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
       advance();
       const int j_nn = c_j;  // needed one tile from now
       int* fs = (t & 1) ? flag_slot1 : flag_slot0;
-      const bool is_tail = ragged && j_cur == p.Tk - 1;
       if constexpr (IMM) {
-        stage<QB, 0, true>(st, ln, smem, j_cur, j_nxt, fs, is_tail, j_prev, pv_on);
-        stage<QB, 1, true>(st, ln, smem, j_cur, j_nxt, fs, is_tail, j_cur, pv_on);
+        stage<QB, 0, true>(st, ln, smem, j_cur, j_nxt, fs, j_tail, j_prev, pv_on);
+        stage<QB, 1, true>(st, ln, smem, j_cur, j_nxt, fs, j_tail, j_cur, pv_on);
         pv_on = !finish_tile_imm(t, j_cur);
         if (pv_on) {
 #pragma unroll
@@ -685,8 +707,8 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
         }
         j_prev = j_cur;
       } else {
-        stage<QB, 0, false>(st, ln, smem, j_cur, j_nxt, fs, is_tail);
-        stage<QB, 1, false>(st, ln, smem, j_cur, j_nxt, fs, is_tail);
+        stage<QB, 0, false>(st, ln, smem, j_cur, j_nxt, fs, j_tail);
+        stage<QB, 1, false>(st, ln, smem, j_cur, j_nxt, fs, j_tail);
         finish_tile(t, j_cur);
       }
       j_cur = j_nxt;
@@ -698,7 +720,7 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
       dma_stage<QB, kVOff + kStageBytes>(ln.vrsrc, ln.vdma, (uint32_t)(j_prev * kTile + kSub) * 2u, ln.lds_wave);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
-      if (pv_on) mma_pv<QB>(st.oacc, st.pw0, smem + kVOff, ln.vread);
+      if (pv_on) mma_pv<QB>(st.oacc, st.pw0, kVOff, ln.vread);
       if (st.grew_prev) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
@@ -707,10 +729,10 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
 #pragma unroll
             for (int r = 0; r < 16; ++r) st.oacc[qb][db][r] *= st.alpha_prev[qb];
       }
-      if (pv_on) mma_pv<QB>(st.oacc, st.pw, smem + kVOff + kStageBytes, ln.vread);
+      if (pv_on) mma_pv<QB>(st.oacc, st.pw, kVOff + kStageBytes, ln.vread);
     } else {
       // drain: O^T += V^T P~^T of the last stage (odd parity buffer)
-      mma_pv<QB>(st.oacc, st.pw, smem + kVOff + kStageBytes, ln.vread);
+      mma_pv<QB>(st.oacc, st.pw, kVOff + kStageBytes, ln.vread);
     }
     __syncthreads();
   }
