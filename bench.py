@@ -21,13 +21,13 @@ TILE_FLOP = 4.0 * 128 * 128 * 128          # QK^T + PV of one live 128x128 tile 
 PEAK_BF16_TFLOPS = 2500.0                  # MI355X dense bf16 MFMA, published
 
 # HBM/fabric bytes per timed launch of lite_attn_fwd_kernel from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of
-# this file with its defaults (counters are not readable from inside the process): mean over the 8 timed launches,
+# this file with its defaults (counters are not readable from inside the process): mean over the 50 timed launches,
 # FETCH_SIZE scaled x2 and WRITE_SIZE x1 by what a 1 GiB device copy reads on the same counters.  The summary with
 # the commands is profiles/lite_attn_fwd_wan14b.txt.  Any other workload, threshold or step count reports null.
-MEASURED_TRAFFIC = {("wan14b", -3.0, 8, 2): {"read_bytes": 83.0e9, "write_bytes": 0.79e9,
-                                             "dense_step_read_bytes": 31.7e9, "sparse_step_read_bytes": 90.3e9,
-                                             "algorithmic_min_bytes": 3.09e9,
-                                             "source": "profiles/lite_attn_fwd_wan14b.txt"}}
+MEASURED_TRAFFIC = {("wan14b", -3.0, 50, 2): {"read_bytes": 87.1e9, "write_bytes": 0.78e9,
+                                              "dense_step_read_bytes": 31.4e9, "sparse_step_read_bytes": 88.3e9,
+                                              "algorithmic_min_bytes": 3.09e9,
+                                              "source": "profiles/lite_attn_fwd_wan14b.txt"}}
 
 # skip threshold (natural-log units of S) used per workload when none is given
 DEFAULT_THRESHOLD = {"tiny": -2.0, "wan1.3b_dense": -float("inf"), "wan1.3b_sweep": -3.0, "wan14b": -3.0,
@@ -61,7 +61,7 @@ def cpu_baseline(wl, q, k, v, threshold, budget_rows):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--steps", type=int, default=None, help="default: the workload's sequence length (wan14b: 50)")
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="wan14b")
     ap.add_argument("--threshold", type=float, default=None)
@@ -79,7 +79,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     wl = inputs.WORKLOADS[args.workload]
     thr = DEFAULT_THRESHOLD[args.workload] if args.threshold is None else args.threshold
-    K, W = args.steps, args.warmup
+    K, W = args.steps or wl.steps, args.warmup
     dev = torch.device("cuda:0")
     B, H, N, d = wl.batch, wl.heads, wl.seqlen, wl.head_dim
     Tq = -(-N // 128)

@@ -46,13 +46,13 @@ typedef enum {
    the visiting order of the j loop decides how soon tiles can be judged against the true maximum (paper: Method,
    "Skipping Condition": other orderings reach the global maximum faster; its experiments use the linear order).
    Default: ascending j.  LITE_ATTN_ORDER_DIAGONAL_FIRST: Q tile i visits K/V tiles i, i+1, ..., Tk-1, 0, ..., i-1. */
-#define LITE_ATTN_ORDER_DIAGONAL_FIRST 1
+#define LITE_ATTN_ORDER_DIAGONAL_FIRST 2
 /* LITE_ATTN_PV_SKIP_IMMEDIATE: the paper's Algorithm 2 taken literally -- a tile whose predicate fires is dropped in
    the very call that marks it (its exp(S) V product and row sums are not accumulated), instead of contributing once
    more and being skipped from the next call on (the default, which is what the paper's Implementation section
    describes for its kernel).  The Skip-Mask after the call is the same in both modes: a fired tile cannot raise the
    running maximum.  The output of the marking call equals attention over the tiles live AFTER the call. */
-#define LITE_ATTN_PV_SKIP_IMMEDIATE 2
+#define LITE_ATTN_PV_SKIP_IMMEDIATE 1
 
 /* Shape of one attention layer; fixed for the life of a handle. */
 typedef struct {

@@ -37,6 +37,10 @@ class Stats(ctypes.Structure):
     ]
 
 
+# desc.flags (include/lite_attn.h)
+LITE_ATTN_PV_SKIP_IMMEDIATE = 1
+LITE_ATTN_ORDER_DIAGONAL_FIRST = 2
+
 _H = ctypes.c_void_p
 _lib.lite_attn_init_mask.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(_H)]
 _lib.lite_attn_set_stream.argtypes = [_H, ctypes.c_void_p]

@@ -61,11 +61,15 @@ def check_step(o_gpu, o_ref, m_gpu, m_ref, g_ref, thr, o_keep=None):
 
 
 def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sample_rows=None, gen_device=None,
-                       verbose=False, seed=0, layout="bhnd", diagonal_first=False, immediate=False):
+                       verbose=False, seed=0, layout="bhnd", diagonal_first=False, immediate=False,
+                       free_running=False):
     """Runs `steps` denoising steps of a named workload on cuda:0 through the C ABI and checks every step.
 
     sample_rows: None = all rows; an int = that many seeded random rows plus first/last (and protected) rows.
     immediate: both sides drop a fired tile in the call that marks it (Algorithm 2 literally).
+    free_running: no teacher forcing -- the HIP path keeps its own mask trajectory.  A compared Q tile whose two entry
+    masks still agree is checked as usual (so the first disagreement of a row has to lie inside the band); rows whose
+    trajectories have parted are only counted ("diverged_rows", "diverged_bits" in the report).
     Returns the list of per-step reports."""
     from paper_2511_11062_amd import lite_attn as la
     wl = inputs.WORKLOADS[workload] if isinstance(workload, str) else workload
@@ -89,13 +93,15 @@ def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sa
     seq = inputs.DriftSequence(wl, gen_device or ("cpu" if B * H * N <= 1 << 16 else dev))
     strides = None if layout == "bhnd" else (N * H * d, d, H * d)       # "bnhd": memory order [B,N,H,d]
     handle = la.lite_attn_init_mask(B, H, N, protect=wl.protect, max_steps=max(steps, 1), strides=strides,
-                                    flags=(1 if diagonal_first else 0) | (2 if immediate else 0))
+                                    flags=(la.LITE_ATTN_ORDER_DIAGONAL_FIRST if diagonal_first else 0) |
+                                    (la.LITE_ATTN_PV_SKIP_IMMEDIATE if immediate else 0))
     visit = None
     if diagonal_first:
         from oracle.lite_attn_oracle import diagonal_first as diag
         visit = diag(Tq, Tk)
     la.lite_attn_set_stream(handle, torch.cuda.current_stream().cuda_stream)
     m_ref = np.zeros((1, len(heads), Tq, Tk), dtype=np.uint8)      # oracle mask of the compared heads
+    m_gpu = np.zeros((len(rows), Tk), dtype=np.uint8)              # HIP mask of the compared rows after the last step
     reports = []
     try:
         for t in range(steps):
@@ -110,13 +116,15 @@ def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sa
                 out_mem = out = torch.empty_like(q)
             qs, ks, vs = (inputs.bf16_bits(x.reshape(B * H, N, d)[heads].unsqueeze(0)) for x in (q, k, v))
             # teacher forcing: compared rows of the HIP mask := oracle's entry mask
-            if t > 0:
+            if t > 0 and not free_running:
                 bits = la.lite_attn_mask_export(handle).reshape(B * H * Tq, W)
                 bits[rows] = pack_mask(m_ref.reshape(-1, Tk)[sub_rows])
                 la.lite_attn_mask_import(handle, bits, t)
             la.lite_attn_fwd(mem[0].data_ptr(), mem[1].data_ptr(), mem[2].data_ptr(), out_mem.data_ptr(), handle,
                              thr, t)
             torch.cuda.synchronize()
+            same = (m_gpu != 0) == (m_ref.reshape(-1, Tk)[sub_rows] != 0)       # entry masks, per compared row
+            row_ok = same.all(axis=1) if free_running else np.ones(len(rows), dtype=bool)
             o_ref, m_new, g = oracle_step(qs, ks, vs, m_ref, thr, protect=wl.protect, rows=sub_rows, visit=visit,
                                           immediate=immediate)
             o_gpu = out.reshape(B * H, N, d)[heads].float().cpu().numpy()
@@ -126,15 +134,19 @@ def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sa
                 sel_o[r // Tq, (r % Tq) * 128:min(N, (r % Tq + 1) * 128)] = True
             g_rows = g.reshape(-1, Tk)[sub_rows]
             o_keep = None
-            if immediate:
+            if immediate or free_running:
                 with np.errstate(invalid="ignore"):
                     near = (np.abs(g_rows - thr) <= G_BAND).any(axis=1)        # per compared Q tile, in sub_rows order
-                keep_tile = {r: not n for r, n in zip(sub_rows, near)}
+                if not immediate:
+                    near[:] = False
+                keep_tile = {r: bool(ok and not n) for r, n, ok in zip(sub_rows, near, row_ok)}
                 tile_of_token = np.zeros((len(heads), N), dtype=np.int64)
                 tile_of_token[:] = np.arange(N) // 128
                 tile_of_token += (np.arange(len(heads)) * Tq)[:, None]
                 o_keep = np.array([keep_tile[int(x)] for x in tile_of_token[sel_o]])
-            rep = check_step(o_gpu[sel_o], o_ref[0][sel_o], m_gpu, m_new.reshape(-1, Tk)[sub_rows], g_rows, thr, o_keep)
+            m_exit = m_new.reshape(-1, Tk)[sub_rows]
+            rep = check_step(o_gpu[sel_o], o_ref[0][sel_o], m_gpu[row_ok], m_exit[row_ok], g_rows[row_ok], thr, o_keep)
+            rep.update(diverged_rows=int((~row_ok).sum()), diverged_bits=int(((m_gpu != 0) != (m_exit != 0)).sum()))
             st = la.lite_attn_skip_stats(handle, t)
             rep.update(step=t, threshold=thr, gpu_skipped_in=st.tiles_skipped_in / st.tiles_total,
                        gpu_newly=st.tiles_newly_marked / st.tiles_total)

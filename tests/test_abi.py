@@ -62,3 +62,13 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     lib.lite_attn_free_mask(None)
     lib.lite_attn_strerror.restype = ctypes.c_char_p
     assert b"step" in lib.lite_attn_strerror(-2)
+
+
+def test_binding_flag_constants_match_the_header():
+    """The Python binding repeats the desc.flags values of the header."""
+    text = open(HEADER).read()
+    defines = dict(re.findall(r"#define\s+(LITE_ATTN_[A-Z_]+)\s+(\d+)", text))
+    src = open(os.path.join(ROOT, "paper_2511_11062_amd", "lite_attn.py")).read()
+    consts = dict(re.findall(r"^(LITE_ATTN_[A-Z_]+)\s*=\s*(\d+)", src, flags=re.M))
+    assert consts and consts == {k: v for k, v in defines.items() if k in consts}
+    assert set(consts) == {"LITE_ATTN_PV_SKIP_IMMEDIATE", "LITE_ATTN_ORDER_DIAGONAL_FIRST"}

@@ -20,6 +20,14 @@ def test_wan13b_sweep_three_steps():
     assert reps[-1]["skipped_out"] > 0.1
 
 
+@pytest.mark.parametrize("threshold,expect", [(-2.75, 0.30), (-1.5, 0.45), (-0.5, 0.60), (-0.1, 0.70)])
+def test_wan13b_sweep_ten_steps_four_thresholds(threshold, expect):
+    """Config 3 in full: the 10-step sequence at each of the four thresholds of the sweep (about 30, 45, 60 and 70 %
+    of the tiles skipped at the end), sampled rows, every step compared."""
+    reps = parity.run_sequence_check("wan1.3b_sweep", steps=10, threshold=threshold, sample_rows=12, seed=3)
+    assert abs(reps[-1]["gpu_skipped_in"] - expect) < 0.03
+
+
 def test_wan14b_two_steps():
     """Config 4: B=1,H=40,N=75600 (tail tile of 80 columns)."""
     reps = parity.run_sequence_check("wan14b", steps=2, threshold=-3.0, sample_rows=10, verbose=True)
