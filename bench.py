@@ -79,7 +79,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     wl = inputs.WORKLOADS[args.workload]
     thr = DEFAULT_THRESHOLD[args.workload] if args.threshold is None else args.threshold
-    K, W = args.steps or wl.steps, args.warmup
+    # default: the workload's whole sequence; a single-step workload (dense check) is repeated 10 times
+    K, W = args.steps or (wl.steps if wl.steps > 1 else 10), args.warmup
     dev = torch.device("cuda:0")
     B, H, N, d = wl.batch, wl.heads, wl.seqlen, wl.head_dim
     Tq = -(-N // 128)
@@ -138,6 +139,7 @@ def main():
         "metric": "dense-equivalent attention TFLOP/s over a denoising sequence (4*B*H*N^2*d per step / time)",
         "value": round(K * dense / wall / 1e12, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(wall / K * 1e3, 3),
+        "median_attn_ms": round(sorted(s_["attn_ms"] + s_["prep_ms"] for s_ in per_step)[K // 2], 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: B=%d H=%d N=%d d=%d, %dx%dx%d latent grid%s, steps 0..%d of a drift sequence" % (
             wl.name, B, H, N, d, wl.grid[0], wl.grid[1], wl.grid[2],
