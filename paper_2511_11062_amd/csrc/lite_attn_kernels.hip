@@ -28,6 +28,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <utility>
+
 #include "lite_attn_kernels.h"
 
 namespace la {
@@ -42,6 +44,12 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 #define LA_LDS __attribute__((address_space(3)))
+
+// f(integral_constant<int, 0>), f(integral_constant<int, 1>), ... : a loop whose index is a constant expression
+template <int... Ks, class F>
+__device__ __forceinline__ void static_for(std::integer_sequence<int, Ks...>, F&& f) {
+  (f(std::integral_constant<int, Ks>{}), ...);
+}
 
 constexpr int kTile = 128;        // Skip-Mask tile: 128 Q rows x 128 K/V columns
 constexpr int kSub = 64;          // K/V columns per pipeline stage
@@ -350,13 +358,14 @@ __device__ __forceinline__ void mma_pv(f32x16 (&oacc)[QB][4], const uint32_t (&p
 }
 
 // LDS -> register fragment k of a stage's matrix work: k < 16 is the V^T fragment (column chunk k/4, d-block k%4)
-// of O^T += V^T P~^T, k >= 16 the K fragment (block k%2, d-chunk (k-16)/2) of S^T(s+1) = K Q^T: the two 32-column
-// blocks alternate, so that consecutive MFMAs never accumulate into the same registers.
+// of O^T += V^T P~^T, k >= 16 the K fragment (block (k-16)/8, d-chunk (k-16)%8) of S^T(s+1) = K Q^T.  Block 1 starts
+// only at step 24, after the softmax has consumed block 1 of the current stage: its accumulators reuse those
+// registers (alternating the two blocks was measured: no faster, six registers more).
 // kread / vread hold absolute LDS addresses (of stage buffer 0), kK / kV are the byte offsets of the stage buffers
 // read: every fragment address is one loop-invariant register plus an immediate.
 template <int kK, int kV>
 __device__ __forceinline__ bf16x8 load_frag(int k, const uint32_t (&kread)[8], const uint32_t (&vread)[4]) {
-  if (k >= 16) return *reinterpret_cast<LA_LDS const bf16x8*>(kread[(k - 16) >> 1] + (uint32_t)(kK + 8192 * (k & 1)));
+  if (k >= 16) return *reinterpret_cast<LA_LDS const bf16x8*>(kread[k & 7] + (uint32_t)(kK + 8192 * ((k - 16) >> 3)));
   const int cc = k >> 2, db = k & 3;
   return *reinterpret_cast<LA_LDS const bf16x8*>(vread[cc] + (uint32_t)(kV + 4096 * db));
 }
@@ -404,12 +413,12 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
   bool ok = true, grew = false;
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
-#pragma unroll
-  for (int k = 0; k < 32; ++k) {
+  static_for(std::make_integer_sequence<int, 32>{}, [&](auto kc) __attribute__((always_inline)) {
+    constexpr int k = decltype(kc)::value;  // the step index is a compile-time constant: every register index is static
     // ---- matrix cores ----
     const bf16x8 a = frag[k % kPrefetch];
     if (k >= 16) {
-      const int blk = k & 1, kk = (k - 16) >> 1;
+      const int blk = (k - 16) >> 3, kk = k & 7;
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         if (kk == 0) {
@@ -497,7 +506,7 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
     }
     if (H && k == 23) *flag_slot = __all(ok) ? 1 : 0;  // lane 0: the wave's slot; other lanes: a dummy word each
     __builtin_amdgcn_sched_barrier(0);
-  }
+  });
   // O^T of the earlier stages is rescaled after this stage's PV MFMAs (rare once the running max has settled).
   // IMM: O^T now holds the products up to stage s-2 and moves to the reference maximum of stage s-1, whose product
   // the next stage adds; this stage's own factor waits one stage.
@@ -832,7 +841,7 @@ hipError_t prepare_fwd() {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lite_attn_fwd_kernel<kQB, false>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, fwd_lds_bytes());
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(lite_attn_fwd_kernel<kQB, true>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(lite_attn_fwd_kernel<1, true>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, fwd_lds_bytes());
 }
 
@@ -848,7 +857,7 @@ hipError_t launch_fwd(const FwdParams& p, bool immediate, hipStream_t st) {
   const int chunks = ((p.Tq + kChunkRows - 1) / kChunkRows) * BH;
   const int per_xcd = ((chunks + 7) / 8) * kChunkRows;
   if (immediate)
-    hipLaunchKernelGGL((lite_attn_fwd_kernel<kQB, true>), dim3(8 * per_xcd), dim3(Geo<kQB>::kThreads), fwd_lds_bytes(),
+    hipLaunchKernelGGL((lite_attn_fwd_kernel<1, true>), dim3(8 * per_xcd), dim3(Geo<1>::kThreads), fwd_lds_bytes(),
                        st, p);
   else
     hipLaunchKernelGGL((lite_attn_fwd_kernel<kQB, false>), dim3(8 * per_xcd), dim3(Geo<kQB>::kThreads), fwd_lds_bytes(),
