@@ -96,7 +96,10 @@ int lite_attn_set_stream(lite_attn_mask_t* mask, void* hip_stream);
                -INFINITY never marks anything (with an empty mask the result is dense attention)
      step      0 clears the mask and the statistics first (new denoising trajectory); otherwise must be the
                previous call's step + 1
-   Asynchronous on the handle's stream; allocates nothing. */
+   Asynchronous on the handle's stream; allocates nothing.  With profiling off (lite_attn_profile) the call only
+   launches kernels -- no memset, memcpy or event nodes -- so a sequence of calls may be captured in a HIP graph; a
+   replay repeats the captured steps (same step numbers, thresholds and pointers); the statistics counters of a
+   replayed step keep adding up unless the replay includes step 0, which clears them. */
 int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_attn_mask_t* skip_mask,
                   float threshold, int step);
 

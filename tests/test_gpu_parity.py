@@ -221,3 +221,58 @@ def test_free_running_trajectories_stay_together():
                                      verbose=True)
     assert reps[-1]["diverged_rows"] <= max(1, len(reps) // 2)
     print("diverged rows per step:", [r["diverged_rows"] for r in reps], "bits:", [r["diverged_bits"] for r in reps])
+
+
+def test_hip_graph_capture_and_replay():
+    """lite_attn_fwd only launches kernels on the handle's stream (the step-0 clear is a fill kernel too), so a
+    sequence of calls can be captured in a HIP graph.  Three steps are captured once and replayed three times, with
+    eager work and synchronisations in between; every replay must reproduce the eager outputs and the eager mask
+    bit for bit (step 0 clears the mask, so each replay starts a fresh trajectory)."""
+    from paper_2511_11062_amd import lite_attn as la
+    wl = small("graph", 2, (2, 20, 31), 3, seed=9)              # N = 1240: ragged tail
+    B, H, N = wl.batch, wl.heads, wl.seqlen
+    dev = torch.device("cuda:0")
+    seq = inputs.DriftSequence(wl, "cpu")
+    data = [tuple(x.to(dev).contiguous() for x in next(seq)) for _ in range(3)]
+    thr = [-3.0, -2.0, -1.0]
+
+    def run(handle, outs):
+        for t, (q, k, v) in enumerate(data):
+            la.lite_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), outs[t].data_ptr(), handle, thr[t], t)
+
+    eager = la.lite_attn_init_mask(B, H, N, max_steps=4)
+    la.lite_attn_set_stream(eager, torch.cuda.current_stream().cuda_stream)
+    ref = [torch.empty_like(data[0][0]) for _ in range(3)]
+    run(eager, ref)
+    torch.cuda.synchronize()
+    ref_mask = la.lite_attn_mask_export(eager).copy()
+    assert ref_mask.any()
+
+    h = la.lite_attn_init_mask(B, H, N, max_steps=4)
+    outs = [torch.empty_like(data[0][0]) for _ in range(3)]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    try:
+        with torch.cuda.stream(side):
+            la.lite_attn_set_stream(h, side.cuda_stream)
+            run(h, outs)                                         # warm-up on the side stream before capture
+            side.synchronize()
+            graph.capture_begin()
+            run(h, outs)
+            graph.capture_end()
+        torch.cuda.synchronize()
+        for rep in range(3):
+            for o in outs:
+                o.zero_()                                        # eager work between replays
+            la.lite_attn_fwd(data[0][0].data_ptr(), data[0][1].data_ptr(), data[0][2].data_ptr(),
+                             ref[0].data_ptr(), eager, thr[0], 0)   # and an eager call on another handle
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for t in range(3):
+                assert torch.equal(outs[t], ref[t]), "replay %d step %d differs" % (rep, t)
+            assert np.array_equal(la.lite_attn_mask_export(h), ref_mask), "replay %d: mask differs" % rep
+    finally:
+        del graph
+        la.lite_attn_free_mask(h)
+        la.lite_attn_free_mask(eager)
