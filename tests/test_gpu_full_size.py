@@ -34,7 +34,32 @@ def test_wan14b_two_steps():
     assert reps[-1]["skipped_out"] > 0.1
 
 
+def test_wan14b_six_steps_growing_mask():
+    """Config 4 shape over six steps with a threshold that rises, so that the mask grows at several steps and the
+    row schedule (rows ranked by Skip-List length) is exercised on masks of different shapes."""
+    reps = parity.run_sequence_check("wan14b", steps=6, thresholds=[-4.0, -3.0, -3.0, -2.0, -2.0, -1.0], sample_rows=8,
+                                     seed=11, verbose=True)
+    frac = [r["skipped_out"] for r in reps]
+    assert frac == sorted(frac) and frac[-1] > 0.4
+
+
+def test_wan14b_diagonal_first_and_immediate():
+    """Config 4 shape with both flags: diagonal-first visiting order and immediate PV-skip."""
+    reps = parity.run_sequence_check("wan14b", steps=3, thresholds=[-3.0, -2.0, -1.0], sample_rows=6, seed=12,
+                                     diagonal_first=True, immediate=True, verbose=True)
+    assert reps[-1]["skipped_out"] > 0.4
+
+
 def test_longvideo_with_text_tokens_two_steps():
     """Config 5: B=1,H=24,N=118800+256 text tokens (931x931 tiles, tail tile of 16 columns, protected range)."""
     reps = parity.run_sequence_check("longvideo", steps=2, threshold=-3.0, sample_rows=8, verbose=True)
     assert reps[-1]["skipped_out"] > 0.1
+
+
+def test_longvideo_four_steps_growing_mask():
+    """Config 5 shape over four steps with a rising threshold; the rows touching the text tokens are among the
+    compared rows and must stay unmarked (the oracle's mask has them pinned)."""
+    reps = parity.run_sequence_check("longvideo", steps=4, thresholds=[-3.0, -2.0, -1.5, -1.0], sample_rows=6, seed=13,
+                                     verbose=True)
+    frac = [r["skipped_out"] for r in reps]          # over the compared rows, several of which are pinned
+    assert frac == sorted(frac) and frac[-1] > 0.3
