@@ -63,3 +63,16 @@ def test_longvideo_four_steps_growing_mask():
                                      verbose=True)
     frac = [r["skipped_out"] for r in reps]          # over the compared rows, several of which are pinned
     assert frac == sorted(frac) and frac[-1] > 0.3
+
+
+def test_wan14b_bench_configuration_all_fifty_steps():
+    """The sequence bench.py times by default (config 4: 50 steps, threshold -3), every step compared on sampled rows."""
+    reps = parity.run_sequence_check("wan14b", steps=50, threshold=-3.0, sample_rows=4, seed=21)
+    assert len(reps) == 50 and 0.25 < reps[-1]["gpu_skipped_in"] < 0.35
+    assert max(r["max_dO"] / r["max_O"] for r in reps) <= parity.MAX_REL
+
+
+def test_longvideo_all_thirty_steps():
+    """Config 5 in full: 30 steps, threshold -3, sampled rows including those that touch the protected text tokens."""
+    reps = parity.run_sequence_check("longvideo", steps=30, threshold=-3.0, sample_rows=3, seed=22)
+    assert len(reps) == 30 and 0.25 < reps[-1]["gpu_skipped_in"] < 0.35
