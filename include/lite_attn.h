@@ -36,7 +36,7 @@ typedef enum {
   LITE_ATTN_OK = 0,
   LITE_ATTN_EINVAL = -1,       /* null pointer, non-positive size, threshold >= 0 or NaN, bad stride */
   LITE_ATTN_ESTEP = -2,        /* step is neither 0 nor last step + 1, or >= max_steps */
-  LITE_ATTN_EUNSUPPORTED = -3, /* head_dim != 128, tile_q/tile_k != 128, more than 65535 K/V tiles, or one head's
+  LITE_ATTN_EUNSUPPORTED = -3, /* head_dim != 128, tile_q/tile_k != 128, more than 16383 K/V tiles (seqlen > 2097024), or one head's
                                   K/V spanning 4 GiB or more ((seqlen+128)*stride_n*2 bytes) */
   LITE_ATTN_ENOMEM = -4,       /* host or device allocation failed */
   LITE_ATTN_EHIP = -5          /* a HIP runtime call failed; lite_attn_last_hip_error() has its code */
@@ -81,7 +81,9 @@ typedef struct {
 
 /* Allocates the handle and its device buffers on the current HIP device and clears the mask.
    Paper: the Skip-Mask is a persistent per-layer, per-head structure (Implementation, "LiteAttention").
-   *out is written only on success.  Uses the null stream until lite_attn_set_stream. */
+   *out is written only on success.  Uses the null stream until lite_attn_set_stream.  The handle belongs to the
+   device that is current here: every later call on it must be made with the same device current.  Calls on one
+   handle are not thread-safe; different handles are independent. */
 int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out);
 
 /* All later work of this handle is enqueued on `hip_stream` (a hipStream_t, e.g. PyTorch's current stream). */
