@@ -76,3 +76,16 @@ def test_longvideo_all_thirty_steps():
     """Config 5 in full: 30 steps, threshold -3, sampled rows including those that touch the protected text tokens."""
     reps = parity.run_sequence_check("longvideo", steps=30, threshold=-3.0, sample_rows=3, seed=22)
     assert len(reps) == 30 and 0.25 < reps[-1]["gpu_skipped_in"] < 0.35
+
+
+def test_maximum_sequence_length():
+    """The longest sequence the library accepts (16383 K/V tiles per row is the limit): one head of N = 2 095 626
+    tokens, 16 373 x 16 373 tiles with a 10-column tail, two steps, sampled rows.  One more tile row is refused."""
+    from paper_2511_11062_amd import inputs, lite_attn as la
+    wl = inputs.Workload("max_len", 1, 1, (13, 401, 402), steps=2, seed=31)
+    assert -(-wl.seqlen // 128) == 16373
+    reps = parity.run_sequence_check(wl, steps=2, threshold=-3.0, sample_rows=2, seed=31)
+    assert reps[1]["gpu_skipped_in"] > 0.1
+    with pytest.raises(la.LiteAttnError) as err:
+        la.lite_attn_init_mask(1, 1, 128 * 16384)
+    assert err.value.code == -3
