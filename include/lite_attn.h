@@ -141,7 +141,7 @@ int lite_attn_mask_import(lite_attn_mask_t* mask, const uint64_t* host_bits, siz
      host_nruns [B*H*Tq] uint32
    Synchronises. */
 int lite_attn_skipruns_export(lite_attn_mask_t* mask, uint32_t* host_runs, uint32_t* host_nruns);
-size_t lite_attn_skipruns_stride(const lite_attn_mask_t* mask); /* entries per row = ceil(Tk/2) */
+size_t lite_attn_skipruns_stride(const lite_attn_mask_t* mask); /* entries per row = floor(Tk/2) + 1 */
 
 /* Same list expanded on the host into packed tile indices:
      host_live_idx [B*H*Tq][Tk] uint16: indices of the row's live K/V tiles, in visiting order, in the first

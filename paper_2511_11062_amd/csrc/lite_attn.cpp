@@ -12,7 +12,8 @@
 struct lite_attn_mask {
   lite_attn_desc_t desc;
   int Tq, Tk, W;
-  int run_stride;   // capacity of one row's run-length Skip-List: a row of Tk tiles has at most ceil(Tk/2) runs
+  int run_stride;   // capacity of one row's run-length Skip-List: Tk/2 + 1 runs (ascending order: at most
+                    // ceil(Tk/2); diagonal first: the wrap at the last tile can split one more, floor(Tk/2) + 1)
   int64_t rows;
   uint64_t* d_bits;
   uint32_t* d_runs;   // [rows][run_stride] start | end << 16
@@ -80,7 +81,7 @@ int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out) {
   m->Tq = (desc->seqlen + desc->tile_q - 1) / desc->tile_q;
   m->Tk = (desc->seqlen + desc->tile_k - 1) / desc->tile_k;
   m->W = (m->Tk + 63) / 64;
-  m->run_stride = (m->Tk + 1) / 2;
+  m->run_stride = m->Tk / 2 + 1;
   m->rows = (int64_t)desc->batch * desc->heads * m->Tq;
   m->stream = nullptr;
   m->next_step = 0;

@@ -167,6 +167,11 @@ def lite_attn_skipruns_export(mask, rows: int):
     return runs, nruns
 
 
+def lite_attn_skipruns_stride(mask) -> int:
+    """Entries per row of the run-length Skip-List."""
+    return int(_lib.lite_attn_skipruns_stride(mask))
+
+
 def lite_attn_free_mask(mask):
     _lib.lite_attn_free_mask(mask)
 

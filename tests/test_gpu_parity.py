@@ -276,3 +276,42 @@ def test_hip_graph_capture_and_replay():
         del graph
         la.lite_attn_free_mask(h)
         la.lite_attn_free_mask(eager)
+
+
+@pytest.mark.parametrize("tiles", [2, 3, 4, 5, 8, 65])
+def test_skiplist_capacity_worst_case_masks(tiles):
+    """The run-length list of a row holds floor(Tk/2) + 1 entries: alternating live/skipped tiles give the most runs,
+    and in diagonal-first order the wrap-around at the last tile can split one more.  Every row here is a worst
+    case; the rows must not spill into each other (several heads, both orders, both phases of the alternation)."""
+    from paper_2511_11062_amd import lite_attn as la
+    B, H, N = 2, 3, 128 * tiles - 5
+    Tq = Tk = tiles
+    for flags in (0, la.LITE_ATTN_ORDER_DIAGONAL_FIRST):
+        h = la.lite_attn_init_mask(B, H, N, flags=flags)
+        try:
+            assert la.lite_attn_skipruns_stride(h) == Tk // 2 + 1
+            for phase in (0, 1):
+                mask = np.zeros((B * H * Tq, Tk), dtype=np.uint8)
+                mask[:, phase::2] = 1                                     # every other tile skipped
+                if phase == 0 and Tk == 1:
+                    mask[:] = 0
+                la.lite_attn_mask_import(h, parity.pack_mask(mask), 1)
+                idx, cnt = la.lite_attn_skiplist_export(h, B * H * Tq, Tk)
+                runs, nruns = la.lite_attn_skipruns_export(h, B * H * Tq)
+                assert int(nruns.max()) <= Tk // 2 + 1
+                for r in range(B * H * Tq):
+                    i = r % Tq if flags else 0
+                    live = np.flatnonzero(mask[r] == 0)
+                    expect = np.concatenate((live[live >= i], live[live < i]))
+                    assert cnt[r] == len(expect) and np.array_equal(idx[r, :cnt[r]], expect), (tiles, flags, phase, r)
+        finally:
+            la.lite_attn_free_mask(h)
+
+
+@pytest.mark.parametrize("n_grid", [(1, 11, 13), (1, 12, 20), (1, 13, 20), (2, 16, 16)])
+def test_diagonal_first_few_tiles_many_heads(n_grid):
+    """Two to four tiles per row, six heads, diagonal-first order: with two tiles the second row's list is two runs
+    long (tile 1, then tile 0) -- the case that needs the extra Skip-List entry."""
+    wl = small("diag_small", 3, n_grid, 2, batch=2, seed=17)
+    parity.run_sequence_check(wl, steps=2, thresholds=[-3.0, -1.0], diagonal_first=True)
+    parity.run_sequence_check(wl, steps=2, thresholds=[-3.0, -1.0], diagonal_first=True, immediate=True)
