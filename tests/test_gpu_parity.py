@@ -315,3 +315,28 @@ def test_diagonal_first_few_tiles_many_heads(n_grid):
     wl = small("diag_small", 3, n_grid, 2, batch=2, seed=17)
     parity.run_sequence_check(wl, steps=2, thresholds=[-3.0, -1.0], diagonal_first=True)
     parity.run_sequence_check(wl, steps=2, thresholds=[-3.0, -1.0], diagonal_first=True, immediate=True)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_randomized_shapes_and_flags(seed):
+    """Forty seeded random cases per seed: batch 1-2, heads 1-3, grids up to 4 x 30 x 40 (N from 24 to a few thousand,
+    ragged), optional protected text tokens, 1-4 steps with random thresholds (some disabled), both memory layouts,
+    either visiting order, deferred or immediate marking, teacher-forced or free-running."""
+    import random
+    rnd = random.Random(seed)
+    for case in range(40):
+        f, h, w = rnd.randint(1, 4), rnd.randint(1, 30), rnd.randint(1, 40)
+        text = rnd.choice([0, 0, 0, rnd.randint(1, 300)])
+        if f * h * w + text < 24:           # below that the absolute mean tolerance sits at bf16 rounding of O(1) outputs
+            w += 24
+        batch, heads, steps = rnd.randint(1, 2), rnd.randint(1, 3), rnd.randint(1, 4)
+        thr = [rnd.choice([NINF, -rnd.uniform(0.2, 4.0)]) for _ in range(steps)]
+        kw = dict(diagonal_first=rnd.random() < 0.4, immediate=rnd.random() < 0.4, free_running=rnd.random() < 0.2,
+                  layout=rnd.choice(["bhnd", "bnhd"]))
+        wl = inputs.Workload("rnd%d_%d" % (seed, case), batch, heads, (f, h, w), text_tokens=text, steps=steps,
+                             seed=rnd.randint(0, 1 << 30))
+        try:
+            parity.run_sequence_check(wl, steps=steps, thresholds=thr, **kw)
+        except AssertionError as e:
+            raise AssertionError("case %d (B=%d H=%d grid=%s text=%d thr=%s %s): %s" % (
+                case, batch, heads, (f, h, w), text, thr, kw, e))
