@@ -85,7 +85,9 @@ def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sa
         base = {0, Tq - 1, B * H * Tq - 1, (B * H - 1) * Tq}
         if wl.text_tokens:
             base |= {wl.video_tokens // 128, wl.video_tokens // 128 - 1, Tq + wl.video_tokens // 128}
+        base = {r for r in base if 0 <= r < B * H * Tq}          # (a single head has no second head's text rows)
         rows = np.array(sorted(base | set(rng.choice(B * H * Tq, size=sample_rows, replace=False).tolist())))
+    assert rows.min() >= 0 and rows.max() < B * H * Tq
     heads = sorted({int(r // Tq) for r in rows})            # flattened (b*H+h)
     head_pos = {bh: n for n, bh in enumerate(heads)}
     sub_rows = [head_pos[int(r // Tq)] * Tq + int(r % Tq) for r in rows]

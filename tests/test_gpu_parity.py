@@ -340,3 +340,48 @@ def test_randomized_shapes_and_flags(seed):
         except AssertionError as e:
             raise AssertionError("case %d (B=%d H=%d grid=%s text=%d thr=%s %s): %s" % (
                 case, batch, heads, (f, h, w), text, thr, kw, e))
+
+
+@pytest.mark.parametrize("diagonal_first", [False, True])
+@pytest.mark.parametrize("density", [0.3, 0.7, 0.95, 1.0])
+def test_arbitrary_imported_masks(density, diagonal_first):
+    """Masks that no predicate produced: random bits at several densities (many one-tile runs, rows with a single
+    live tile, rows with none at all) are imported into both sides; with marking disabled the outputs must agree and
+    the masks must come back unchanged.  density 1.0 = every tile skipped: all-zero output."""
+    from oracle.lite_attn_oracle import oracle_step, diagonal_first as diag
+    from paper_2511_11062_amd import lite_attn as la
+    rng = np.random.default_rng(int(density * 100) + (7 if diagonal_first else 0))
+    wl = small("rand_mask", 3, (3, 29, 55), 1, batch=1, seed=23)          # N = 4785: 38 tiles, 49-column tail
+    B, H, N, d = wl.batch, wl.heads, wl.seqlen, wl.head_dim
+    Tq = Tk = -(-N // 128)
+    q, k, v = (x.cuda().contiguous() for x in next(inputs.DriftSequence(wl, "cpu")))
+    mask = (rng.random((B, H, Tq, Tk)) < density).astype(np.uint8)
+    if density < 1.0:
+        mask[0, 0, 5, :] = 1
+        mask[0, 0, 5, 17] = 0                                             # a row with exactly one live tile
+        mask[0, 1, 9, :] = 1                                              # a row with none
+    flags = la.LITE_ATTN_ORDER_DIAGONAL_FIRST if diagonal_first else 0
+    h = la.lite_attn_init_mask(B, H, N, flags=flags, max_steps=3)
+    try:
+        la.lite_attn_mask_import(h, parity.pack_mask(mask.reshape(-1, Tk)), 1)
+        out = torch.empty_like(q)
+        la.lite_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), h, NINF, 1)
+        torch.cuda.synchronize()
+        bits = la.lite_attn_mask_export(h)
+        st = la.lite_attn_skip_stats(h, 1)
+    finally:
+        la.lite_attn_free_mask(h)
+    assert np.array_equal(parity.unpack_mask(bits.reshape(-1, (Tk + 63) // 64), Tk), mask.reshape(-1, Tk))
+    assert st.tiles_skipped_in == int(mask.sum()) and st.tiles_newly_marked == 0
+    m_ref = mask.copy()
+    o_ref, m_new, _ = oracle_step(*(inputs.bf16_bits(x) for x in (q, k, v)), m_ref, NINF,
+                                  visit=diag(Tq, Tk) if diagonal_first else None)
+    assert np.array_equal(m_new, mask)
+    o_gpu = out.float().cpu().numpy()
+    empty = mask.all(axis=-1)                                             # [B,H,Tq] rows without a live tile
+    for b, hh, i in zip(*np.nonzero(empty)):
+        assert not o_gpu[b, hh, i * 128:(i + 1) * 128].any()
+    keep = np.repeat(~empty, 128, axis=-1)[..., :N]
+    if keep.any():
+        mx, mean, omax = parity.compare_output(o_gpu[keep], o_ref[keep])
+        assert mx <= parity.MAX_REL * omax and mean <= parity.MEAN_ABS, (mx, mean, omax)
