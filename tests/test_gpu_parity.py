@@ -421,3 +421,42 @@ def test_row_schedule_covers_every_row(heads, tiles):
         err = (out[0, hh].float() - ref).abs().max().item()
         worst = max(worst, err / max(ref.abs().max().item(), 1e-6))
     assert worst <= parity.MAX_REL, worst
+
+
+def test_two_handles_on_two_streams():
+    """Two layers' handles driven on two streams at the same time give what each gives alone (the library keeps no
+    state outside the handle)."""
+    from paper_2511_11062_amd import lite_attn as la
+    wls = [small("layer_a", 3, (3, 20, 33), 3, seed=41), small("layer_b", 2, (2, 31, 47), 3, seed=42)]
+    data = []
+    for wl in wls:
+        seq = inputs.DriftSequence(wl, "cpu")
+        data.append([tuple(x.cuda().contiguous() for x in next(seq)) for _ in range(3)])
+    thr = [-3.0, -2.0, -1.0]
+
+    def run_all(streams):
+        hs = [la.lite_attn_init_mask(wl.batch, wl.heads, wl.seqlen, max_steps=4) for wl in wls]
+        outs = [[torch.empty_like(d[0]) for d in layer] for layer in data]
+        try:
+            for hdl, s in zip(hs, streams):
+                la.lite_attn_set_stream(hdl, s.cuda_stream)
+            for t in range(3):
+                for n, (hdl, s) in enumerate(zip(hs, streams)):
+                    q, k, v = data[n][t]
+                    la.lite_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), outs[n][t].data_ptr(), hdl, thr[t], t)
+            torch.cuda.synchronize()
+            masks = [la.lite_attn_mask_export(hdl).copy() for hdl in hs]
+        finally:
+            for hdl in hs:
+                la.lite_attn_free_mask(hdl)
+        return outs, masks
+
+    cur = torch.cuda.current_stream()
+    serial_o, serial_m = run_all([cur, cur])
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    par_o, par_m = run_all([s1, s2])
+    for n in range(2):
+        assert np.array_equal(serial_m[n], par_m[n]) and serial_m[n].any()
+        for t in range(3):
+            assert torch.equal(serial_o[n][t], par_o[n][t])
