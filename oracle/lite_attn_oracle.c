@@ -31,10 +31,12 @@
  * output given a live set; an O(N^2) prefix-max formula for every predicate
  * value; a closed-form two-tile case; the bound max P~ <= e^thr on fired
  * tiles; monotone mask, first live tile never fires, pinned tiles never fire,
- * deferred and immediate modes give equal masks.  The multi-step mask
- * trajectory on synthetic data has no value printed in the paper to compare
- * with: beyond those pins it is "parity unpinned" -- the oracle is the
- * definition.
+ * deferred and immediate modes give equal masks; a five-step trajectory
+ * (masks and outputs of every step) against the same loop composed from the
+ * O(N^2) float64 definitions alone.  The paper prints no worked numeric
+ * example, so no pin compares with a value of the paper's: in that sense
+ * the multi-step trajectory on the synthetic data stays "parity unpinned"
+ * -- it is pinned to the definitions, not to published numbers.
  */
 #include <math.h>
 #include <stdint.h>

@@ -202,6 +202,48 @@ def test_mask_evolution_invariants():
     assert counts == sorted(counts) and counts[0] > 0 and counts[-1] > counts[0]
 
 
+@pytest.mark.parametrize("immediate", [False, True])
+def test_multi_step_trajectory_matches_brute_force(immediate):
+    """The whole denoising loop, composed from the O(N^2) definitions alone: per step the predicate of every tile
+    live on entry comes from the prefix-max formula over the dense S, the next mask is entry | (g <= thr) without
+    the pinned tiles, and the output is dense attention over the tiles live on entry (deferred) or on exit
+    (immediate).  The oracle, fed only the inputs, must walk the same masks and give the same outputs at every step
+    (no tile here lies within 1e-6 of its threshold, so the fp64 trajectories cannot part).
+    Catches: anything wrong in how the steps chain -- mask not carried, bits cleared, fired tiles seen or not seen by
+    the next step's running max, pinned range applied to one side only."""
+    H, N, d, t, steps = 2, 448, 32, 64, 5
+    thrs = [-0.9, -0.7, -0.5, -0.4, -0.3]
+    protect = (300, 40)                                                # tokens 300..339: tiles 4 and 5
+    data = _drift_steps(19, H, N, d, steps)
+    T = N // t
+    pinned = np.zeros((T, T), dtype=bool)
+    for x in range(T):
+        if x * t < protect[0] + protect[1] and protect[0] < (x + 1) * t:
+            pinned[x, :] = True
+            pinned[:, x] = True
+    mask = empty_mask(1, H, N, t, t)
+    brute_mask = np.zeros((H, T, T), dtype=np.uint8)
+    grew = []
+    for (q, k, v), thr in zip(data, thrs):
+        out, mask_new, _ = oracle_step(q, k, v, mask, thr, tile_q=t, tile_k=t, protect=protect, immediate=immediate,
+                                       f64=True)
+        for h in range(H):
+            qh, kh, vh = (brute.widen(x[0, h]) for x in (q, k, v))
+            g = brute.predicate_values(qh, kh, brute_mask[h], t, t)
+            with np.errstate(invalid="ignore"):
+                assert not (np.abs(g - thr) < 1e-6).any()
+                fired = (g <= thr) & ~pinned
+            exit_mask = brute_mask[h] | fired.astype(np.uint8)
+            live = (exit_mask == 0) if immediate else (brute_mask[h] == 0)
+            ref = brute.dense_attention(qh, kh, vh, brute.expand_tiles(live, t, t, N))
+            assert np.array_equal(mask_new[0, h] != 0, exit_mask != 0)
+            assert np.abs(out[0, h] - ref).max() <= 1e-11
+            brute_mask[h] = exit_mask
+        grew.append(int(brute_mask.sum()))
+        mask = mask_new
+    assert grew[0] > 0 and grew[-1] > grew[0] and not brute_mask[:, pinned].any(), grew
+
+
 def test_first_tile_never_fires_when_all_scores_are_negative():
     """m_{i,-1} is -inf, not 0: with every score negative the first live tile still has g = 0."""
     rng = np.random.default_rng(11)
