@@ -93,7 +93,10 @@ def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sa
     sub_rows = [head_pos[int(r // Tq)] * Tq + int(r % Tq) for r in rows]
 
     seq = inputs.DriftSequence(wl, gen_device or ("cpu" if B * H * N <= 1 << 16 else dev))
-    strides = None if layout == "bhnd" else (N * H * d, d, H * d)       # "bnhd": memory order [B,N,H,d]
+    # "bnhd": memory order [B,N,H,d]; "padded": [B,H,N,d+8] with 8 unused elements after every token row, and a gap
+    # of 64 elements after every head
+    pad_n, pad_h = d + 8, N * (d + 8) + 64
+    strides = {"bhnd": None, "bnhd": (N * H * d, d, H * d), "padded": (H * pad_h, pad_h, pad_n)}[layout]
     handle = la.lite_attn_init_mask(B, H, N, protect=wl.protect, max_steps=max(steps, 1), strides=strides,
                                     flags=(la.LITE_ATTN_ORDER_DIAGONAL_FIRST if diagonal_first else 0) |
                                     (la.LITE_ATTN_PV_SKIP_IMMEDIATE if immediate else 0))
@@ -113,6 +116,16 @@ def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sa
                 mem = [x.permute(0, 2, 1, 3).contiguous() for x in (q, k, v)]
                 out_mem = torch.empty_like(mem[0])
                 out = out_mem.permute(0, 2, 1, 3)
+            elif layout == "padded":
+                def padded(x=None):
+                    buf = torch.full((B * H * pad_h,), float("nan"), dtype=torch.bfloat16, device=dev)
+                    view = torch.as_strided(buf, (B, H, N, d), (H * pad_h, pad_h, pad_n, 1))
+                    if x is not None:
+                        view.copy_(x)
+                    view.whole_buffer = buf
+                    return view
+                mem = [padded(x) for x in (q, k, v)]                   # the gaps hold NaN: nothing may read them
+                out_mem = out = padded()
             else:
                 mem = [q, k, v]
                 out_mem = out = torch.empty_like(q)
@@ -130,6 +143,10 @@ def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sa
             o_ref, m_new, g = oracle_step(qs, ks, vs, m_ref, thr, protect=wl.protect, rows=sub_rows, visit=visit,
                                           immediate=immediate)
             o_gpu = out.reshape(B * H, N, d)[heads].float().cpu().numpy()
+            if layout == "padded":                                     # nothing was written into the gaps of `out`
+                untouched = torch.isnan(out.whole_buffer.float())
+                torch.as_strided(untouched, (B, H, N, d), (H * pad_h, pad_h, pad_n, 1)).fill_(True)
+                assert bool(untouched.all()), "the kernel wrote outside the rows of `out`"
             m_gpu = unpack_mask(la.lite_attn_mask_export(handle).reshape(B * H * Tq, W), Tk)[rows]
             sel_o = np.zeros((len(heads), N), dtype=bool)
             for r in sub_rows:

@@ -29,7 +29,7 @@ def test_rising_thresholds_grow_the_mask():
         assert abs(b["gpu_skipped_in"] - a["skipped_out"]) < 1e-12   # teacher-forced entry mask = oracle's exit mask
 
 
-@pytest.mark.parametrize("layout", ["bhnd", "bnhd"])
+@pytest.mark.parametrize("layout", ["bhnd", "bnhd", "padded"])
 @pytest.mark.parametrize("n_grid", [(1, 1, 1), (1, 5, 17), (1, 8, 16), (3, 10, 30), (2, 24, 31)])
 def test_dense_ragged_shapes(n_grid, layout):
     """Threshold disabled: the result is dense softmax attention (paper eqs. 1-3); N = 1, 85, 128, 900, 1488."""
@@ -460,3 +460,12 @@ def test_two_handles_on_two_streams():
         assert np.array_equal(serial_m[n], par_m[n]) and serial_m[n].any()
         for t in range(3):
             assert torch.equal(serial_o[n][t], par_o[n][t])
+
+
+def test_padded_strides_multi_step():
+    """Token rows 8 elements apart from dense packing and heads 64 elements apart: three steps with skipping; the gaps
+    are filled with NaN (never read) and must still be NaN in the output buffer (never written)."""
+    wl = small("padded_seq", 3, (2, 24, 31), 3, batch=2)
+    reps = parity.run_sequence_check(wl, steps=3, thresholds=[-3.0, -2.0, -1.0], layout="padded", verbose=True)
+    assert reps[-1]["skipped_out"] > 0.05
+    parity.run_sequence_check(wl, steps=2, thresholds=[-2.0, -1.0], layout="padded", diagonal_first=True, immediate=True)
