@@ -89,7 +89,8 @@ int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out);
 /* All later work of this handle is enqueued on `hip_stream` (a hipStream_t, e.g. PyTorch's current stream). */
 int lite_attn_set_stream(lite_attn_mask_t* mask, void* hip_stream);
 
-/* One attention call (Algorithm 2 with the deferred mask update, see top of file).
+/* One attention call (Algorithm 2 with the deferred mask update, see top of file; desc.flags selects the
+   immediate variant and the visiting order).
      q, k, v   device bf16, layout given by the handle's strides; borrowed, not modified; values must be finite
                (the kernels are built with the assumption that no NaN occurs)
      out       device bf16, same layout; every valid row is written
