@@ -36,8 +36,8 @@ typedef enum {
   LITE_ATTN_OK = 0,
   LITE_ATTN_EINVAL = -1,       /* null pointer, non-positive size, threshold >= 0 or NaN, bad stride */
   LITE_ATTN_ESTEP = -2,        /* step is neither 0 nor last step + 1, or >= max_steps */
-  LITE_ATTN_EUNSUPPORTED = -3, /* head_dim != 128, tile_q/tile_k != 128, more than 16383 K/V tiles (seqlen > 2097024), or one head's
-                                  K/V spanning 4 GiB or more ((seqlen+128)*stride_n*2 bytes) */
+  LITE_ATTN_EUNSUPPORTED = -3, /* head_dim != 128, tile_q/tile_k != 128, more than 16383 K/V tiles (seqlen >
+                                  2097024), or one head's K/V spanning 4 GiB or more ((seqlen+128)*stride_n*2 bytes) */
   LITE_ATTN_ENOMEM = -4,       /* host or device allocation failed */
   LITE_ATTN_EHIP = -5          /* a HIP runtime call failed; lite_attn_last_hip_error() has its code */
 } lite_attn_error;

@@ -48,7 +48,8 @@ int check_desc(const lite_attn_desc_t* d) {
   if (!d) return LITE_ATTN_EINVAL;
   if (d->batch < 1 || d->heads < 1 || d->seqlen < 1 || d->head_dim < 1 || d->tile_q < 1 || d->tile_k < 1)
     return LITE_ATTN_EINVAL;
-  if (d->max_steps < 1 || (d->flags & ~(LITE_ATTN_ORDER_DIAGONAL_FIRST | LITE_ATTN_PV_SKIP_IMMEDIATE)) != 0) return LITE_ATTN_EINVAL;
+  if (d->max_steps < 1) return LITE_ATTN_EINVAL;
+  if ((d->flags & ~(LITE_ATTN_ORDER_DIAGONAL_FIRST | LITE_ATTN_PV_SKIP_IMMEDIATE)) != 0) return LITE_ATTN_EINVAL;
   if (d->protect_len < 0 || d->protect_start < 0 ||
       (d->protect_len > 0 && (int64_t)d->protect_start + d->protect_len > d->seqlen))
     return LITE_ATTN_EINVAL;
@@ -88,7 +89,8 @@ int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out) {
   m->profile = false;
   m->events = nullptr;
   m->timed = nullptr;
-  m->d_bits = nullptr; m->d_runs = nullptr; m->d_nruns = nullptr; m->d_live_cnt = nullptr; m->d_stats = nullptr; m->d_vt = nullptr; m->d_order = nullptr;
+  m->d_bits = nullptr; m->d_runs = nullptr; m->d_nruns = nullptr; m->d_live_cnt = nullptr;
+  m->d_stats = nullptr; m->d_vt = nullptr; m->d_order = nullptr;
   hipError_t e = hipMalloc(&m->d_bits, sizeof(uint64_t) * (size_t)m->rows * m->W);
   if (e == hipSuccess) e = hipMalloc(&m->d_runs, sizeof(uint32_t) * (size_t)m->rows * m->run_stride);
   if (e == hipSuccess) e = hipMalloc(&m->d_nruns, sizeof(uint32_t) * (size_t)m->rows);
@@ -130,8 +132,8 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
   hipEvent_t* ev = (m->profile && m->events) ? m->events + 3 * (size_t)step : nullptr;
   if (m->timed) m->timed[step] = ev != nullptr;
   if (ev) LA_HIP(hipEventRecord(ev[0], m->stream));
-  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tq, m->Tk, m->W, d.flags & LITE_ATTN_ORDER_DIAGONAL_FIRST, m->run_stride,
-                            m->d_runs, m->d_nruns, m->d_live_cnt, st, st + 2, m->stream));
+  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tq, m->Tk, m->W, d.flags & LITE_ATTN_ORDER_DIAGONAL_FIRST,
+                            m->run_stride, m->d_runs, m->d_nruns, m->d_live_cnt, st, st + 2, m->stream));
   LA_HIP(la::launch_order_rows(m->d_live_cnt, d.batch * d.heads, m->Tq, m->Tk, m->d_order, m->stream));
   LA_HIP(la::launch_transpose_v(static_cast<const uint16_t*>(v), m->d_vt, d.stride_b, d.stride_h, d.stride_n,
                                 d.batch * d.heads, d.heads, d.seqlen, m->Tk, m->stream));

@@ -3,8 +3,11 @@
 //   clear_state_kernel   : zero the Skip-Mask and the statistics (step 0)
 //   compact_skiplist     : Skip-Mask row -> run-length list of its live K/V tiles, (start,end) per run
 //                          (Implementation, "Producer and Skip-List Optimization")
+//   order_rows_kernel    : per head, Q-tile rows ranked by Skip-List length (the launch order of the fused kernel)
+//   transpose_v_kernel   : V -> V^T scratch, so that the PV operand is read from LDS like the QK operand
 //   lite_attn_fwd_kernel : fused tiled forward over the live tiles with the skip predicate
 //                          (Algorithm 2; eq. sparge_cond; tile recurrences of the Preliminaries)
+//   mfma_peak_kernel     : register-resident MFMA loop (benchmark diagnostic)
 //
 // Fused kernel, one workgroup (4 wave64) = one Q tile = one Skip-Mask row:
 //   * wave w owns Q rows [32w, 32w+32); lane l owns Q row (l & 31) of them.
@@ -69,9 +72,10 @@ __global__ void clear_state_kernel(uint64_t* bits, size_t words, unsigned long l
   for (size_t x = i; x < nstats; x += stride) stats[x] = 0;
 }
 
-// Skip-List compaction, one wave per Q-tile row (a wave takes kRowsPerWave consecutive rows).  The list is run-length encoded as the paper describes: one entry
-// (start | end << 16) per maximal run of consecutive live K/V tiles [start, end), in visiting order (ascending, or
-// -- "diagonal first" -- the tiles from the diagonal one to the last, then those before the diagonal).  Lane l looks at bit l of each
+// Skip-List compaction, one wave per Q-tile row (a wave takes kRowsPerWave consecutive rows).  The list is run-length
+// encoded as the paper describes: one entry (start | end << 16) per maximal run of consecutive live K/V tiles
+// [start, end), in visiting order (ascending, or -- "diagonal first" -- the tiles from the diagonal one to the last,
+// then those before the diagonal; a row then has at most floor(Tk/2) + 1 runs).  Lane l looks at bit l of each
 // 64-tile word: a live tile whose predecessor is not live starts a run, one whose successor is not live ends it;
 // the k-th start and the k-th end of a row belong to the same run, so the two 16-bit halves are written
 // independently at the position given by a ballot + prefix popcount.

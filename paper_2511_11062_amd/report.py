@@ -28,7 +28,8 @@ def run_sequence(wl, data, thresholds, dense_out=None, diagonal_first=False, imm
     computed against it; otherwise the outputs are returned (used to produce the dense reference)."""
     B, H, N = wl.batch, wl.heads, wl.seqlen
     steps = len(data)
-    flags = (la.LITE_ATTN_ORDER_DIAGONAL_FIRST if diagonal_first else 0) | (la.LITE_ATTN_PV_SKIP_IMMEDIATE if immediate else 0)
+    flags = ((la.LITE_ATTN_ORDER_DIAGONAL_FIRST if diagonal_first else 0) |
+             (la.LITE_ATTN_PV_SKIP_IMMEDIATE if immediate else 0))
     h = la.lite_attn_init_mask(B, H, N, protect=wl.protect, max_steps=steps, flags=flags)
     la.lite_attn_set_stream(h, torch.cuda.current_stream().cuda_stream)
     la.lite_attn_profile(h, True)
@@ -64,7 +65,8 @@ def main():
     ap.add_argument("--diagonal-first", action="store_true",
                     help="visit the K/V tiles of Q tile i in the order i, i+1, ..., Tk-1, 0, ..., i-1")
     ap.add_argument("--immediate", action="store_true",
-                    help="drop a fired tile in the call that marks it (Algorithm 2 literally) instead of from the next call on")
+                    help="drop a fired tile in the call that marks it (Algorithm 2 literally) instead of from the next "
+                         "call on")
     args = ap.parse_args()
     wl = inputs.WORKLOADS[args.workload]
     steps = args.steps or wl.steps
@@ -72,7 +74,8 @@ def main():
     data = [next(seq) for _ in range(steps)]
     thresholds = args.thresholds or SWEEP_THRESHOLDS.get(wl.name, [-4.0, -3.0, -2.0, -1.0])
     dense_out, dense_rows = run_sequence(wl, data, [-float("inf")] * steps)
-    result = {"workload": wl.name, "steps": steps, "diagonal_first": args.diagonal_first, "immediate": args.immediate, "dense_ms": [r["attn_ms"] for r in dense_rows], "runs": []}
+    result = {"workload": wl.name, "steps": steps, "diagonal_first": args.diagonal_first, "immediate": args.immediate,
+              "dense_ms": [r["attn_ms"] for r in dense_rows], "runs": []}
     for thr in thresholds:
         _, rows = run_sequence(wl, data, [thr] * steps, dense_out, args.diagonal_first, args.immediate)
         result["runs"].append({"threshold": thr, "per_step": rows})
