@@ -413,7 +413,7 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
   for (int k = 0; k < kPrefetch; ++k)
     if (!IMM || pv_on) frag[k] = load_frag<kKSrc, kVSrc>(k, ln.kread, ln.vread);
 
-  float pm[QB][4], mx[QB], m_new[QB], mc[QB], alpha[QB], lsum[QB];
+  float pm[QB][4], mx[QB], m_new[QB], mc[QB], alpha[QB], lsum[QB], ta0[QB], ta1[QB], tb0[QB];
   bool ok = true, grew = false;
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
@@ -490,18 +490,32 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
         st.m_run[qb] = m_new[qb];
         mc[qb] = m_new[qb] * ln.c;
         lsum[qb] = 0.f;
-      } else if (k < 22) {  // P~ = exp(S - m_ij) for two scores, packed to bf16
-        const int e = k - 6, blk = e >> 3, r = 2 * (e & 7);
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[qb][blk][r], ln.c, -mc[qb]));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[qb][blk][r + 1], ln.c, -mc[qb]));
-        uint32_t w = pack_bf16x2(p0, p1);
-        // the row sum adds the bf16-rounded weights, the same values the PV product uses
-        lsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, lsum[qb], false);
-        // an empty volatile asm pins this slice to step k: without it the compiler sinks all the exponentials
-        // behind the last MFMA, where nothing overlaps them
-        asm volatile("" : "+v"(w), "+v"(lsum[qb]));
-        pwc[qb][e] = w;  // word e belongs to chunk e/4, whose last reader was the MFMA of step 4*(e/4)+3 < k
-      } else if (k == 22) {
+      } else if (k < 30) {
+        // P~ = exp(S - m_ij), packed to bf16: 16 pairs of scores over 24 steps, four vector instructions per step
+        // (a cycle of three steps does two pairs: exp exp | pack+sum, exp | exp, pack+sum)
+        const int t = k - 6, c = t / 3, ph = t % 3;
+        const int eA = 2 * c, eB = 2 * c + 1;
+        if (ph == 0) {
+          ta0[qb] = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[qb][eA >> 3][2 * (eA & 7)], ln.c, -mc[qb]));
+          ta1[qb] = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[qb][eA >> 3][2 * (eA & 7) + 1], ln.c, -mc[qb]));
+          // empty volatile asms pin every slice to its step: without them the compiler sinks all the exponentials
+          // behind the last MFMA, where nothing overlaps them
+          asm volatile("" : "+v"(ta0[qb]), "+v"(ta1[qb]));
+        } else if (ph == 1) {
+          uint32_t w = pack_bf16x2(ta0[qb], ta1[qb]);
+          // the row sum adds the bf16-rounded weights, the same values the PV product uses
+          lsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, lsum[qb], false);
+          tb0[qb] = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[qb][eB >> 3][2 * (eB & 7)], ln.c, -mc[qb]));
+          asm volatile("" : "+v"(w), "+v"(lsum[qb]), "+v"(tb0[qb]));
+          pwc[qb][eA] = w;  // word e belongs to chunk e/4, whose last reader was the MFMA of step 4*(e/4)+3 < k
+        } else {
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[qb][eB >> 3][2 * (eB & 7) + 1], ln.c, -mc[qb]));
+          uint32_t w = pack_bf16x2(tb0[qb], p1);
+          lsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, lsum[qb], false);
+          asm volatile("" : "+v"(w), "+v"(lsum[qb]));
+          pwc[qb][eB] = w;
+        }
+      } else if (k == 30) {
         if (IMM) {
           st.l_run[qb] *= alpha[qb];
           st.l_pend[qb] = H ? st.l_pend[qb] * alpha[qb] + lsum[qb] : lsum[qb];
@@ -514,7 +528,7 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
         }
       }
     }
-    if (H && k == 23) *flag_slot = __all(ok) ? 1 : 0;  // lane 0: the wave's slot; other lanes: a dummy word each
+    if (H && k == 31) *flag_slot = __all(ok) ? 1 : 0;  // lane 0: the wave's slot; other lanes: a dummy word each
   };
   static_for(std::make_integer_sequence<int, 32>{}, [&](auto kc) __attribute__((always_inline)) {
     // matrix instruction and the memory instructions of the step first, then (fenced) the vector slice: measured
