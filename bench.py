@@ -117,6 +117,20 @@ def main():
     mfma_peak_measured = la.lite_attn_mfma_peak(stream, data[0][2].data_ptr())
     mfma_peak_k = la.lite_attn_mfma_peak(stream, data[0][1][0, 0, N // 2].data_ptr())
 
+    # the same kernel on all-zero operands (dense, one launch after a warm-up): the instruction stream is identical,
+    # only the power drawn by the matrix cores differs -- what the issue structure allows when the clock does not drop
+    zeros = torch.zeros_like(data[0][0])
+    zout = torch.empty_like(zeros)
+    zh = la.lite_attn_init_mask(B, H, N, protect=wl.protect, max_steps=2)
+    la.lite_attn_set_stream(zh, stream)
+    la.lite_attn_profile(zh, True)
+    for t in range(2):
+        la.lite_attn_fwd(zeros.data_ptr(), zeros.data_ptr(), zeros.data_ptr(), zout.data_ptr(), zh, -float("inf"), t)
+    torch.cuda.synchronize()
+    zero_ms = la.lite_attn_kernel_times(zh, 1)[1]
+    la.lite_attn_free_mask(zh)
+    del zeros, zout
+
     per_step = []
     live_flop = 0.0
     fwd_ms_total = 0.0
@@ -157,6 +171,9 @@ def main():
                      "measured_mfma_only_tflops": round(mfma_peak_measured, 1),
                      "measured_mfma_only_tflops_on_k": round(mfma_peak_k, 1),
                      "frac_of_measured_mfma_only": round(achieved / mfma_peak_measured, 4),
+                     "dense_step_on_zero_operands": {"ms": round(zero_ms, 3),
+                                                     "tflops": round(wl.dense_flops() / zero_ms / 1e9, 1),
+                                                     "frac": round(wl.dense_flops() / zero_ms / 1e9 / PEAK_BF16_TFLOPS, 4)},
                      "note": "achieved = 8.39 MFLOP x live tiles of the K timed launches / their summed HIP-event "
                              "durations"},
     }
