@@ -24,8 +24,8 @@ PEAK_BF16_TFLOPS = 2500.0                  # MI355X dense bf16 MFMA, published
 # this file with its defaults (counters are not readable from inside the process): mean over the 50 timed launches,
 # FETCH_SIZE scaled x2 and WRITE_SIZE x1 by what a 1 GiB device copy reads on the same counters.  The summary with
 # the commands is profiles/lite_attn_fwd_wan14b.txt.  Any other workload, threshold or step count reports null.
-MEASURED_TRAFFIC = {("wan14b", -3.0, 50, 2): {"read_bytes": 87.1e9, "write_bytes": 0.78e9,
-                                              "dense_step_read_bytes": 31.4e9, "sparse_step_read_bytes": 88.3e9,
+MEASURED_TRAFFIC = {("wan14b", -3.0, 50, 2): {"read_bytes": 91.8e9, "write_bytes": 0.78e9,
+                                              "dense_step_read_bytes": 33.9e9, "sparse_step_read_bytes": 93.0e9,
                                               "algorithmic_min_bytes": 3.09e9,
                                               "source": "profiles/lite_attn_fwd_wan14b.txt"}}
 
