@@ -39,7 +39,9 @@ typedef enum {
   LITE_ATTN_EUNSUPPORTED = -3, /* head_dim != 128, tile_q/tile_k != 128, more than 16383 K/V tiles (seqlen >
                                   2097024), or one head's K/V spanning 4 GiB or more ((seqlen+128)*stride_n*2 bytes) */
   LITE_ATTN_ENOMEM = -4,       /* host or device allocation failed */
-  LITE_ATTN_EHIP = -5          /* a HIP runtime call failed; lite_attn_last_hip_error() has its code */
+  LITE_ATTN_EHIP = -5,         /* a HIP runtime call failed; lite_attn_last_hip_error() has its code */
+  LITE_ATTN_ESHARED = -6       /* refused because scratch is shared: lite_attn_set_stream on a handle of a context with
+                                  any stream but the context's; lite_attn_ctx_free while handles are attached */
 } lite_attn_error;
 
 /* desc.flags.  The skip predicate compares a tile with the running row maximum over the tiles visited BEFORE it, so
@@ -67,7 +69,8 @@ typedef struct {
 } lite_attn_desc_t;
 
 /* Opaque handle: owns the device Skip-Mask ([B,H,Tq,ceil(Tk/64)] uint64, bit j%64 of word j/64 set = tile (i,j)
-   skipped), the Skip-List buffers, a scratch copy of V^T (same size as V) and the statistics.
+   skipped) and the statistics, and owns or borrows (lite_attn_init_mask_shared) the per-call scratch: Skip-List
+   buffers and a copy of V^T (same size as V).
    Tq = ceil(N/tile_q), Tk = ceil(N/tile_k). */
 typedef struct lite_attn_mask lite_attn_mask_t;
 
@@ -86,8 +89,30 @@ typedef struct {
    handle are not thread-safe; different handles are independent. */
 int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out);
 
-/* All later work of this handle is enqueued on `hip_stream` (a hipStream_t, e.g. PyTorch's current stream). */
+/* All later work of this handle is enqueued on `hip_stream` (a hipStream_t, e.g. PyTorch's current stream).
+   For a handle created with lite_attn_init_mask_shared this is refused (LITE_ATTN_ESHARED) unless `hip_stream`
+   is its context's stream: set the stream on the context. */
 int lite_attn_set_stream(lite_attn_mask_t* mask, void* hip_stream);
+
+/* Scratch shared by the layers of a model (this library's own arrangement, nothing of the paper's).
+   A call needs device scratch that nothing reads after the call has finished: the Skip-List, the row schedule and
+   a transposed copy of V, together about the size of V.  A handle made by lite_attn_init_mask owns its own; a model
+   with one handle per layer would hold that once per layer.  Handles made by lite_attn_init_mask_shared borrow the
+   scratch of a context instead: one buffer on the context's device, grown to the largest layer attached so far.
+   Sharing is safe because all handles of a context run on the context's ONE stream, where calls are serial:
+     lite_attn_ctx_create       context on the current HIP device, null stream, no scratch yet
+     lite_attn_ctx_set_stream   waits for the work queued on the old stream, then every handle of the context
+                                (present and future) enqueues on `hip_stream`
+     lite_attn_init_mask_shared like lite_attn_init_mask, the handle attached to `ctx`; may reallocate the shared
+                                scratch (after waiting for the context's stream).  The handle's Skip-Mask and
+                                statistics stay its own.
+     lite_attn_ctx_free         LITE_ATTN_ESHARED while handles are attached (free them first); null is a no-op
+   Calls on one context and its handles are not thread-safe. */
+typedef struct lite_attn_ctx lite_attn_ctx_t;
+int lite_attn_ctx_create(lite_attn_ctx_t** out);
+int lite_attn_ctx_set_stream(lite_attn_ctx_t* ctx, void* hip_stream);
+int lite_attn_init_mask_shared(const lite_attn_desc_t* desc, lite_attn_ctx_t* ctx, lite_attn_mask_t** out);
+int lite_attn_ctx_free(lite_attn_ctx_t* ctx);
 
 /* One attention call (Algorithm 2 with the deferred mask update, see top of file; desc.flags selects the
    immediate variant and the visiting order).
@@ -117,13 +142,6 @@ int lite_attn_skip_stats(lite_attn_mask_t* mask, int step, lite_attn_stats_t* ho
    stream and fails with LITE_ATTN_ESTEP if that step was not run with profiling enabled. */
 int lite_attn_profile(lite_attn_mask_t* mask, int enable);
 int lite_attn_kernel_times(lite_attn_mask_t* mask, int step, float* host_prep_ms, float* host_fwd_ms);
-
-/* Benchmark diagnostic: times a register-resident loop of v_mfma_f32_32x32x16_bf16 (no memory traffic, 2 waves per
-   SIMD on every CU) whose A/B operands are taken from `dev_operands` (device pointer, at least 64 KiB, read as bf16).
-   The sustained matrix-core clock depends on the operands' bit patterns (power), so this is the practical ceiling
-   of the fused kernel on the same kind of data.  Runs `iters` x 32 MFMAs per wave on `hip_stream`, synchronises,
-   and returns the elapsed milliseconds and the flop count. */
-int lite_attn_mfma_peak(void* hip_stream, const void* dev_operands, int iters, float* host_ms, double* host_flops);
 
 /* Number of uint64 words of the whole mask: B*H*Tq*ceil(Tk/64). */
 size_t lite_attn_mask_words(const lite_attn_mask_t* mask);

@@ -23,8 +23,13 @@ _LOCK = threading.Lock()
 _LIBS: dict = {}
 
 
+# LA_ORACLE_SANITIZE=1 (set by tests/test_sanitizers.py for a child process that preloads the sanitizer runtime):
+# build and load an AddressSanitizer + UndefinedBehaviorSanitizer flavour of the same source instead
+_SANITIZE = os.environ.get("LA_ORACLE_SANITIZE") == "1"
+
+
 def _lib_path(f64: bool) -> str:
-    return os.path.join(_HERE, "liblite_attn_oracle_%s.so" % ("f64" if f64 else "f32"))
+    return os.path.join(_HERE, "liblite_attn_oracle_%s%s.so" % ("f64" if f64 else "f32", "_san" if _SANITIZE else ""))
 
 
 def build(force: bool = False) -> None:
@@ -34,6 +39,8 @@ def build(force: bool = False) -> None:
         if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
             continue
         cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra"]
+        if _SANITIZE:
+            cmd += ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-g"]
         if f64:
             cmd.append("-DLA_ORACLE_F64")
         cmd += [_SRC, "-o", out, "-lm"]

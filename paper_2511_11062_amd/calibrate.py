@@ -30,9 +30,10 @@ def _fwd(handle, q, k, v, out, thr, step):
     la.lite_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), handle, thr, step)
 
 
-def calibrate(wl, data, xi=0.075, tau=0.01, lo=-12.0, hi=-0.05, iters=8):
+def calibrate(wl, data, xi=0.075, tau=0.01, lo=-12.0, hi=-0.05, iters=8, keep_masks=False):
     """data: list of (q,k,v) bf16 device tensors, one per timestep.  Returns a list of per-step dicts with the chosen
-    threshold, its eta, the bound, and the skip ratio it leaves behind."""
+    threshold, its eta, the bound, and the skip ratio it leaves behind (keep_masks: also "mask_bits", the exported
+    Skip-Mask words that the step's threshold leaves behind)."""
     B, H, N = wl.batch, wl.heads, wl.seqlen
     T = len(data)
     bounds = [xi - tau if 3 * t < T else (xi if 3 * t < 2 * T else xi + tau) for t in range(T)]
@@ -78,6 +79,8 @@ def calibrate(wl, data, xi=0.075, tau=0.01, lo=-12.0, hi=-0.05, iters=8):
             skipped = int(np.unpackbits(best_mask.view(np.uint8)).sum())
             schedule.append({"step": t, "bound": bounds[t], "threshold": best_thr, "eta": best_eta,
                              "skipped_after": skipped / (B * H * (-(-N // 128)) ** 2), "met": best_eta <= bounds[t]})
+            if keep_masks:
+                schedule[-1]["mask_bits"] = best_mask.copy()
     finally:
         la.lite_attn_free_mask(dense)
         la.lite_attn_free_mask(work)

@@ -1,4 +1,5 @@
-// Host side of the C ABI declared in include/lite_attn.h: handle, argument checks, launches.
+// Host side of the C ABI declared in include/lite_attn.h: handles, contexts, launches (argument checks and the
+// scratch layout are in lite_attn_host.cpp).
 #include "lite_attn.h"
 
 #include <hip/hip_runtime.h>
@@ -9,20 +10,29 @@
 
 #include "lite_attn_kernels.h"
 
+// Device memory that every call rebuilds from scratch (nothing in it outlives a call): the Skip-List, the row
+// schedule and V^T.  A handle either owns one or borrows its context's.
+struct la_scratch {
+  void* base = nullptr;
+  size_t bytes = 0;
+};
+
+struct lite_attn_ctx {
+  la_scratch scratch;
+  hipStream_t stream = nullptr;
+  int device = 0;
+  int handles = 0;  // live handles attached to this context
+};
+
 struct lite_attn_mask {
   lite_attn_desc_t desc;
-  int Tq, Tk, W;
-  int run_stride;   // capacity of one row's run-length Skip-List: Tk/2 + 1 runs (ascending order: at most
-                    // ceil(Tk/2); diagonal first: the wrap at the last tile can split one more, floor(Tk/2) + 1)
-  int64_t rows;
+  la::Geometry geo;
+  la::ScratchLayout lay;
   uint64_t* d_bits;
-  uint32_t* d_runs;   // [rows][run_stride] start | end << 16
-  uint32_t* d_nruns;  // [rows]
-  uint32_t* d_live_cnt;
-  uint32_t* d_order;  // [B*H][Tq] rows of each head ranked by Skip-List length
-  uint16_t* d_vt;  // V^T scratch of the current call: [B*H][128][128*Tk] bf16
   unsigned long long* d_stats;  // [max_steps][3]: skipped on entry, newly marked, Skip-List runs
-  hipStream_t stream;
+  la_scratch own;               // used when ctx == nullptr
+  lite_attn_ctx* ctx;           // shared scratch + stream, or nullptr
+  hipStream_t stream;           // used when ctx == nullptr
   int next_step;
   bool profile;
   hipEvent_t* events;  // [max_steps][3] once profiling was enabled: before the pre-passes, between, after attention
@@ -30,41 +40,123 @@ struct lite_attn_mask {
 };
 
 namespace {
-
 thread_local int g_last_hip = 0;
+}
+
+namespace la {
 
 int hip_fail(hipError_t e) {
   g_last_hip = (int)e;
   return e == hipErrorOutOfMemory ? LITE_ATTN_ENOMEM : LITE_ATTN_EHIP;
 }
 
-#define LA_HIP(expr)                        \
-  do {                                      \
-    hipError_t e_ = (expr);                 \
+hipError_t launch_call(const lite_attn_desc_t& d, const Geometry& g, const ScratchLayout& lay, char* scratch,
+                       const void* q, const void* k, const void* v, void* out, uint64_t* bits,
+                       unsigned long long* stats3, float threshold, hipStream_t stream, hipEvent_t mid) {
+  uint32_t* runs = reinterpret_cast<uint32_t*>(scratch + lay.runs);
+  uint32_t* nruns = reinterpret_cast<uint32_t*>(scratch + lay.nruns);
+  uint32_t* live_cnt = reinterpret_cast<uint32_t*>(scratch + lay.live_cnt);
+  uint32_t* order = reinterpret_cast<uint32_t*>(scratch + lay.order);
+  uint16_t* vt = reinterpret_cast<uint16_t*>(scratch + lay.vt);
+  hipError_t e = launch_compact(bits, (int)g.rows, g.Tq, g.Tk, g.W, d.flags & LITE_ATTN_ORDER_DIAGONAL_FIRST,
+                                g.run_stride, runs, nruns, live_cnt, stats3, stats3 + 2, stream);
+  if (e != hipSuccess) return e;
+  e = launch_order_rows(live_cnt, g.BH, g.Tq, g.Tk, order, stream);
+  if (e != hipSuccess) return e;
+  e = launch_transpose_v(static_cast<const uint16_t*>(v), vt, d.stride_b, d.stride_h, d.stride_n, g.BH, d.heads,
+                         d.seqlen, g.Tk, stream);
+  if (e != hipSuccess) return e;
+  FwdParams p;
+  p.q = static_cast<const uint16_t*>(q);
+  p.k = static_cast<const uint16_t*>(k);
+  p.vt = vt;
+  p.out = static_cast<uint16_t*>(out);
+  p.stride_b = d.stride_b; p.stride_h = d.stride_h; p.stride_n = d.stride_n;
+  p.H = d.heads; p.N = d.seqlen; p.Tq = g.Tq; p.Tk = g.Tk; p.W = g.W;
+  p.runs = runs; p.run_stride = g.run_stride; p.nruns = nruns; p.live_cnt = live_cnt;
+  p.bits = bits;
+  p.stat_newly = stats3 + 1;
+  p.thr = threshold;
+  p.scale = 1.0f / std::sqrt((float)d.head_dim);
+  p.protect_start = d.protect_start; p.protect_len = d.protect_len;
+  p.rows_total = (int)g.rows;
+  p.order = order;
+  if (mid) {
+    e = hipEventRecord(mid, stream);
+    if (e != hipSuccess) return e;
+  }
+  return launch_fwd(p, (d.flags & LITE_ATTN_PV_SKIP_IMMEDIATE) != 0, stream);
+}
+
+}  // namespace la
+
+namespace {
+
+using la::hip_fail;
+
+#define LA_HIP(expr)                           \
+  do {                                         \
+    hipError_t e_ = (expr);                    \
     if (e_ != hipSuccess) return hip_fail(e_); \
   } while (0)
 
-int check_desc(const lite_attn_desc_t* d) {
-  if (!d) return LITE_ATTN_EINVAL;
-  if (d->batch < 1 || d->heads < 1 || d->seqlen < 1 || d->head_dim < 1 || d->tile_q < 1 || d->tile_k < 1)
-    return LITE_ATTN_EINVAL;
-  if (d->max_steps < 1) return LITE_ATTN_EINVAL;
-  if ((d->flags & ~(LITE_ATTN_ORDER_DIAGONAL_FIRST | LITE_ATTN_PV_SKIP_IMMEDIATE)) != 0) return LITE_ATTN_EINVAL;
-  if (d->protect_len < 0 || d->protect_start < 0 ||
-      (d->protect_len > 0 && (int64_t)d->protect_start + d->protect_len > d->seqlen))
-    return LITE_ATTN_EINVAL;
-  // 16-byte vector accesses: every stride must be a multiple of 8 bf16 elements
-  if (d->stride_n < d->head_dim || d->stride_b < 0 || d->stride_h < 0) return LITE_ATTN_EINVAL;
-  if ((d->stride_n % 8) || (d->stride_b % 8) || (d->stride_h % 8)) return LITE_ATTN_EINVAL;
-  if (d->batch > 1 && d->stride_b == 0) return LITE_ATTN_EINVAL;
-  if (d->heads > 1 && d->stride_h == 0) return LITE_ATTN_EINVAL;
-  if (d->head_dim != 128 || d->tile_q != 128 || d->tile_k != 128) return LITE_ATTN_EUNSUPPORTED;
-  const int64_t Tk = ((int64_t)d->seqlen + 127) / 128;
-  if (Tk > 16383) return LITE_ATTN_EUNSUPPORTED;  // row-schedule histogram (Tk + 1 bins) lives in 64 KB of LDS
-  // K/V stages are addressed with 32-bit byte offsets from the head's base pointer
-  if (((int64_t)d->seqlen + 128) * d->stride_n * 2 >= ((int64_t)1 << 32)) return LITE_ATTN_EUNSUPPORTED;
-  const int64_t rows = (int64_t)d->batch * d->heads * Tk;
-  if (rows > (int64_t)1 << 30) return LITE_ATTN_EUNSUPPORTED;
+hipStream_t stream_of(const lite_attn_mask* m) { return m->ctx ? m->ctx->stream : m->stream; }
+char* scratch_of(const lite_attn_mask* m) { return static_cast<char*>(m->ctx ? m->ctx->scratch.base : m->own.base); }
+
+int grow(la_scratch* s, size_t bytes) {
+  if (bytes <= s->bytes) return LITE_ATTN_OK;
+  if (s->base) LA_HIP(hipFree(s->base));
+  s->base = nullptr;
+  s->bytes = 0;
+  LA_HIP(hipMalloc(&s->base, bytes));
+  s->bytes = bytes;
+  return LITE_ATTN_OK;
+}
+
+int init_common(const lite_attn_desc_t* desc, lite_attn_ctx* ctx, lite_attn_mask_t** out) {
+  if (!out) return LITE_ATTN_EINVAL;
+  int rc = la::check_desc(desc);
+  if (rc != LITE_ATTN_OK) return rc;
+  lite_attn_mask* m = new (std::nothrow) lite_attn_mask();
+  if (!m) return LITE_ATTN_ENOMEM;
+  m->desc = *desc;
+  m->geo = la::geometry(*desc);
+  m->lay = la::scratch_layout(m->geo);
+  m->ctx = nullptr;
+  m->stream = nullptr;
+  m->next_step = 0;
+  m->profile = false;
+  m->events = nullptr;
+  m->timed = nullptr;
+  m->d_bits = nullptr;
+  m->d_stats = nullptr;
+  const size_t words = (size_t)m->geo.rows * m->geo.W, nstats = 3 * (size_t)desc->max_steps;
+  hipStream_t st = ctx ? ctx->stream : nullptr;
+  rc = LITE_ATTN_OK;
+  if (ctx) {
+    // every call made so far through this context has to finish before its scratch may move
+    hipError_t e = m->lay.total > ctx->scratch.bytes ? hipStreamSynchronize(ctx->stream) : hipSuccess;
+    rc = e != hipSuccess ? hip_fail(e) : grow(&ctx->scratch, m->lay.total);
+  } else {
+    rc = grow(&m->own, m->lay.total);
+  }
+  if (rc == LITE_ATTN_OK) {
+    hipError_t e = hipMalloc(&m->d_bits, sizeof(uint64_t) * words);
+    if (e == hipSuccess) e = hipMalloc(&m->d_stats, sizeof(unsigned long long) * nstats);
+    if (e == hipSuccess) e = la::prepare_fwd();
+    if (e == hipSuccess) e = la::launch_clear(m->d_bits, words, m->d_stats, nstats, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) rc = hip_fail(e);
+  }
+  if (rc != LITE_ATTN_OK) {
+    lite_attn_free_mask(m);
+    return rc;
+  }
+  if (ctx) {
+    m->ctx = ctx;
+    ++ctx->handles;
+  }
+  *out = m;
   return LITE_ATTN_OK;
 }
 
@@ -72,47 +164,45 @@ int check_desc(const lite_attn_desc_t* d) {
 
 extern "C" {
 
-int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out) {
+int lite_attn_init_mask(const lite_attn_desc_t* desc, lite_attn_mask_t** out) { return init_common(desc, nullptr, out); }
+
+int lite_attn_ctx_create(lite_attn_ctx_t** out) {
   if (!out) return LITE_ATTN_EINVAL;
-  int rc = check_desc(desc);
-  if (rc != LITE_ATTN_OK) return rc;
-  lite_attn_mask* m = new (std::nothrow) lite_attn_mask();
-  if (!m) return LITE_ATTN_ENOMEM;
-  m->desc = *desc;
-  m->Tq = (desc->seqlen + desc->tile_q - 1) / desc->tile_q;
-  m->Tk = (desc->seqlen + desc->tile_k - 1) / desc->tile_k;
-  m->W = (m->Tk + 63) / 64;
-  m->run_stride = m->Tk / 2 + 1;
-  m->rows = (int64_t)desc->batch * desc->heads * m->Tq;
-  m->stream = nullptr;
-  m->next_step = 0;
-  m->profile = false;
-  m->events = nullptr;
-  m->timed = nullptr;
-  m->d_bits = nullptr; m->d_runs = nullptr; m->d_nruns = nullptr; m->d_live_cnt = nullptr;
-  m->d_stats = nullptr; m->d_vt = nullptr; m->d_order = nullptr;
-  hipError_t e = hipMalloc(&m->d_bits, sizeof(uint64_t) * (size_t)m->rows * m->W);
-  if (e == hipSuccess) e = hipMalloc(&m->d_runs, sizeof(uint32_t) * (size_t)m->rows * m->run_stride);
-  if (e == hipSuccess) e = hipMalloc(&m->d_nruns, sizeof(uint32_t) * (size_t)m->rows);
-  if (e == hipSuccess) e = hipMalloc(&m->d_live_cnt, sizeof(uint32_t) * (size_t)m->rows);
-  if (e == hipSuccess) e = hipMalloc(&m->d_order, sizeof(uint32_t) * (size_t)m->rows);
-  if (e == hipSuccess)
-    e = hipMalloc(&m->d_vt, sizeof(uint16_t) * (size_t)desc->batch * desc->heads * 128 * ((size_t)m->Tk * 128));
-  if (e == hipSuccess) e = hipMalloc(&m->d_stats, sizeof(unsigned long long) * 3 * (size_t)desc->max_steps);
-  if (e == hipSuccess) e = la::prepare_fwd();
-  if (e == hipSuccess)
-    e = la::launch_clear(m->d_bits, (size_t)m->rows * m->W, m->d_stats, 3 * (size_t)desc->max_steps, m->stream);
-  if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+  lite_attn_ctx* c = new (std::nothrow) lite_attn_ctx();
+  if (!c) return LITE_ATTN_ENOMEM;
+  hipError_t e = hipGetDevice(&c->device);
   if (e != hipSuccess) {
-    lite_attn_free_mask(m);
+    delete c;
     return hip_fail(e);
   }
-  *out = m;
+  *out = c;
+  return LITE_ATTN_OK;
+}
+
+int lite_attn_ctx_set_stream(lite_attn_ctx_t* ctx, void* hip_stream) {
+  if (!ctx) return LITE_ATTN_EINVAL;
+  LA_HIP(hipStreamSynchronize(ctx->stream));  // work already queued keeps its order with what follows
+  ctx->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  return LITE_ATTN_OK;
+}
+
+int lite_attn_init_mask_shared(const lite_attn_desc_t* desc, lite_attn_ctx_t* ctx, lite_attn_mask_t** out) {
+  if (!ctx) return LITE_ATTN_EINVAL;
+  return init_common(desc, ctx, out);
+}
+
+int lite_attn_ctx_free(lite_attn_ctx_t* ctx) {
+  if (!ctx) return LITE_ATTN_OK;
+  if (ctx->handles != 0) return LITE_ATTN_ESHARED;
+  if (ctx->scratch.base) (void)hipFree(ctx->scratch.base);
+  delete ctx;
   return LITE_ATTN_OK;
 }
 
 int lite_attn_set_stream(lite_attn_mask_t* m, void* hip_stream) {
   if (!m) return LITE_ATTN_EINVAL;
+  if (m->ctx)  // the scratch is only safe while every handle of the context runs on the context's one stream
+    return reinterpret_cast<hipStream_t>(hip_stream) == m->ctx->stream ? LITE_ATTN_OK : LITE_ATTN_ESHARED;
   LA_HIP(hipStreamSynchronize(m->stream));  // work already queued keeps its order with what follows
   m->stream = reinterpret_cast<hipStream_t>(hip_stream);
   return LITE_ATTN_OK;
@@ -120,41 +210,22 @@ int lite_attn_set_stream(lite_attn_mask_t* m, void* hip_stream) {
 
 int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_attn_mask_t* m, float threshold,
                   int step) {
-  if (!q || !k || !v || !out || !m) return LITE_ATTN_EINVAL;
-  if (std::isnan(threshold) || threshold >= 0.f) return LITE_ATTN_EINVAL;
-  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) return LITE_ATTN_EINVAL;
+  if (!m) return LITE_ATTN_EINVAL;
+  int rc = la::check_call(q, k, v, out, threshold);
+  if (rc != LITE_ATTN_OK) return rc;
   if (step < 0 || step >= m->desc.max_steps) return LITE_ATTN_ESTEP;
   if (step != 0 && step != m->next_step) return LITE_ATTN_ESTEP;
   const lite_attn_desc_t& d = m->desc;
+  hipStream_t stream = stream_of(m);
   if (step == 0)
-    LA_HIP(la::launch_clear(m->d_bits, (size_t)m->rows * m->W, m->d_stats, 3 * (size_t)d.max_steps, m->stream));
+    LA_HIP(la::launch_clear(m->d_bits, (size_t)m->geo.rows * m->geo.W, m->d_stats, 3 * (size_t)d.max_steps, stream));
   unsigned long long* st = m->d_stats + 3 * (size_t)step;
   hipEvent_t* ev = (m->profile && m->events) ? m->events + 3 * (size_t)step : nullptr;
   if (m->timed) m->timed[step] = ev != nullptr;
-  if (ev) LA_HIP(hipEventRecord(ev[0], m->stream));
-  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tq, m->Tk, m->W, d.flags & LITE_ATTN_ORDER_DIAGONAL_FIRST,
-                            m->run_stride, m->d_runs, m->d_nruns, m->d_live_cnt, st, st + 2, m->stream));
-  LA_HIP(la::launch_order_rows(m->d_live_cnt, d.batch * d.heads, m->Tq, m->Tk, m->d_order, m->stream));
-  LA_HIP(la::launch_transpose_v(static_cast<const uint16_t*>(v), m->d_vt, d.stride_b, d.stride_h, d.stride_n,
-                                d.batch * d.heads, d.heads, d.seqlen, m->Tk, m->stream));
-  la::FwdParams p;
-  p.q = static_cast<const uint16_t*>(q);
-  p.k = static_cast<const uint16_t*>(k);
-  p.vt = m->d_vt;
-  p.out = static_cast<uint16_t*>(out);
-  p.stride_b = d.stride_b; p.stride_h = d.stride_h; p.stride_n = d.stride_n;
-  p.H = d.heads; p.N = d.seqlen; p.Tq = m->Tq; p.Tk = m->Tk; p.W = m->W;
-  p.runs = m->d_runs; p.run_stride = m->run_stride; p.nruns = m->d_nruns; p.live_cnt = m->d_live_cnt;
-  p.bits = m->d_bits;
-  p.stat_newly = st + 1;
-  p.thr = threshold;
-  p.scale = 1.0f / std::sqrt((float)d.head_dim);
-  p.protect_start = d.protect_start; p.protect_len = d.protect_len;
-  p.rows_total = (int)m->rows;
-  p.order = m->d_order;
-  if (ev) LA_HIP(hipEventRecord(ev[1], m->stream));
-  LA_HIP(la::launch_fwd(p, (d.flags & LITE_ATTN_PV_SKIP_IMMEDIATE) != 0, m->stream));
-  if (ev) LA_HIP(hipEventRecord(ev[2], m->stream));
+  if (ev) LA_HIP(hipEventRecord(ev[0], stream));
+  LA_HIP(la::launch_call(d, m->geo, m->lay, scratch_of(m), q, k, v, out, m->d_bits, st, threshold, stream,
+                         ev ? ev[1] : nullptr));
+  if (ev) LA_HIP(hipEventRecord(ev[2], stream));
   m->next_step = step + 1;
   return LITE_ATTN_OK;
 }
@@ -163,10 +234,10 @@ int lite_attn_skip_stats(lite_attn_mask_t* m, int step, lite_attn_stats_t* host_
   if (!m || !host_out) return LITE_ATTN_EINVAL;
   if (step < 0 || step >= m->next_step || step >= m->desc.max_steps) return LITE_ATTN_ESTEP;
   unsigned long long raw[3];
-  LA_HIP(hipMemcpyAsync(raw, m->d_stats + 3 * (size_t)step, sizeof raw, hipMemcpyDeviceToHost, m->stream));
-  LA_HIP(hipStreamSynchronize(m->stream));
+  LA_HIP(hipMemcpyAsync(raw, m->d_stats + 3 * (size_t)step, sizeof raw, hipMemcpyDeviceToHost, stream_of(m)));
+  LA_HIP(hipStreamSynchronize(stream_of(m)));
   host_out->step = step;
-  host_out->tiles_total = (uint64_t)m->rows * (uint64_t)m->Tk;
+  host_out->tiles_total = (uint64_t)m->geo.rows * (uint64_t)m->geo.Tk;
   host_out->tiles_skipped_in = raw[0];
   host_out->tiles_newly_marked = raw[1];
   host_out->live_list_bytes = raw[2] * sizeof(uint32_t);
@@ -210,75 +281,55 @@ int lite_attn_kernel_times(lite_attn_mask_t* m, int step, float* host_prep_ms, f
   return LITE_ATTN_OK;
 }
 
-int lite_attn_mfma_peak(void* hip_stream, const void* dev_operands, int iters, float* host_ms, double* host_flops) {
-  if (!dev_operands || !host_ms || !host_flops || iters < 1 || iters > (1 << 20)) return LITE_ATTN_EINVAL;
-  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
-  int dev = 0, cus = 0;
-  LA_HIP(hipGetDevice(&dev));
-  LA_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-  const int blocks = 2 * cus;  // 2 workgroups of 4 waves per CU: 2 waves per SIMD
-  float* sink = nullptr;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  hipError_t e = hipMalloc(&sink, sizeof(float));
-  if (e == hipSuccess) e = hipEventCreate(&e0);
-  if (e == hipSuccess) e = hipEventCreate(&e1);
-  if (e == hipSuccess) e = la::launch_mfma_peak(dev_operands, sink, 64, blocks, st);  // warm-up
-  if (e == hipSuccess) e = hipEventRecord(e0, st);
-  if (e == hipSuccess) e = la::launch_mfma_peak(dev_operands, sink, iters, blocks, st);
-  if (e == hipSuccess) e = hipEventRecord(e1, st);
-  if (e == hipSuccess) e = hipEventSynchronize(e1);
-  if (e == hipSuccess) e = hipEventElapsedTime(host_ms, e0, e1);
-  if (e0) (void)hipEventDestroy(e0);
-  if (e1) (void)hipEventDestroy(e1);
-  if (sink) (void)hipFree(sink);
-  if (e != hipSuccess) return hip_fail(e);
-  *host_flops = (double)blocks * 4.0 * (double)iters * 32.0 * (2.0 * 32 * 32 * 16);
-  return LITE_ATTN_OK;
-}
-
-size_t lite_attn_mask_words(const lite_attn_mask_t* m) { return m ? (size_t)m->rows * m->W : 0; }
+size_t lite_attn_mask_words(const lite_attn_mask_t* m) { return m ? (size_t)m->geo.rows * m->geo.W : 0; }
 
 int lite_attn_mask_export(lite_attn_mask_t* m, uint64_t* host_bits, size_t words) {
   if (!m || !host_bits || words != lite_attn_mask_words(m)) return LITE_ATTN_EINVAL;
-  LA_HIP(hipMemcpyAsync(host_bits, m->d_bits, words * sizeof(uint64_t), hipMemcpyDeviceToHost, m->stream));
-  LA_HIP(hipStreamSynchronize(m->stream));
+  LA_HIP(hipMemcpyAsync(host_bits, m->d_bits, words * sizeof(uint64_t), hipMemcpyDeviceToHost, stream_of(m)));
+  LA_HIP(hipStreamSynchronize(stream_of(m)));
   return LITE_ATTN_OK;
 }
 
 int lite_attn_mask_import(lite_attn_mask_t* m, const uint64_t* host_bits, size_t words, int next_step) {
   if (!m || !host_bits || words != lite_attn_mask_words(m)) return LITE_ATTN_EINVAL;
   if (next_step < 0 || next_step >= m->desc.max_steps) return LITE_ATTN_ESTEP;
-  LA_HIP(hipMemcpyAsync(m->d_bits, host_bits, words * sizeof(uint64_t), hipMemcpyHostToDevice, m->stream));
-  LA_HIP(hipStreamSynchronize(m->stream));
+  LA_HIP(hipMemcpyAsync(m->d_bits, host_bits, words * sizeof(uint64_t), hipMemcpyHostToDevice, stream_of(m)));
+  LA_HIP(hipStreamSynchronize(stream_of(m)));
   m->next_step = next_step;
   return LITE_ATTN_OK;
 }
 
 int lite_attn_skipruns_export(lite_attn_mask_t* m, uint32_t* host_runs, uint32_t* host_nruns) {
   if (!m || !host_runs || !host_nruns) return LITE_ATTN_EINVAL;
-  LA_HIP(la::launch_compact(m->d_bits, (int)m->rows, m->Tq, m->Tk, m->W,
-                            m->desc.flags & LITE_ATTN_ORDER_DIAGONAL_FIRST, m->run_stride, m->d_runs, m->d_nruns,
-                            m->d_live_cnt, nullptr, nullptr, m->stream));
-  LA_HIP(hipMemcpyAsync(host_runs, m->d_runs, sizeof(uint32_t) * (size_t)m->rows * m->run_stride,
-                        hipMemcpyDeviceToHost, m->stream));
-  LA_HIP(hipMemcpyAsync(host_nruns, m->d_nruns, sizeof(uint32_t) * (size_t)m->rows, hipMemcpyDeviceToHost, m->stream));
-  LA_HIP(hipStreamSynchronize(m->stream));
+  const la::Geometry& g = m->geo;
+  char* s = scratch_of(m);
+  uint32_t* runs = reinterpret_cast<uint32_t*>(s + m->lay.runs);
+  uint32_t* nruns = reinterpret_cast<uint32_t*>(s + m->lay.nruns);
+  hipStream_t stream = stream_of(m);
+  LA_HIP(la::launch_compact(m->d_bits, (int)g.rows, g.Tq, g.Tk, g.W, m->desc.flags & LITE_ATTN_ORDER_DIAGONAL_FIRST,
+                            g.run_stride, runs, nruns, reinterpret_cast<uint32_t*>(s + m->lay.live_cnt), nullptr,
+                            nullptr, stream));
+  LA_HIP(hipMemcpyAsync(host_runs, runs, sizeof(uint32_t) * (size_t)g.rows * g.run_stride, hipMemcpyDeviceToHost,
+                        stream));
+  LA_HIP(hipMemcpyAsync(host_nruns, nruns, sizeof(uint32_t) * (size_t)g.rows, hipMemcpyDeviceToHost, stream));
+  LA_HIP(hipStreamSynchronize(stream));
   return LITE_ATTN_OK;
 }
 
-size_t lite_attn_skipruns_stride(const lite_attn_mask_t* m) { return m ? (size_t)m->run_stride : 0; }
+size_t lite_attn_skipruns_stride(const lite_attn_mask_t* m) { return m ? (size_t)m->geo.run_stride : 0; }
 
 int lite_attn_skiplist_export(lite_attn_mask_t* m, uint16_t* host_live_idx, uint32_t* host_live_cnt) {
   if (!m || !host_live_idx || !host_live_cnt) return LITE_ATTN_EINVAL;
-  uint32_t* runs = new (std::nothrow) uint32_t[(size_t)m->rows * m->run_stride];
-  uint32_t* nruns = new (std::nothrow) uint32_t[(size_t)m->rows];
+  const la::Geometry& g = m->geo;
+  uint32_t* runs = new (std::nothrow) uint32_t[(size_t)g.rows * g.run_stride];
+  uint32_t* nruns = new (std::nothrow) uint32_t[(size_t)g.rows];
   int rc = (runs && nruns) ? lite_attn_skipruns_export(m, runs, nruns) : LITE_ATTN_ENOMEM;
   if (rc == LITE_ATTN_OK) {
-    for (int64_t row = 0; row < m->rows; ++row) {  // expand the runs into the packed index list
+    for (int64_t row = 0; row < g.rows; ++row) {  // expand the runs into the packed index list
       uint32_t n = 0;
       for (uint32_t x = 0; x < nruns[row]; ++x) {
-        const uint32_t e = runs[row * m->run_stride + x];
-        for (uint32_t j = e & 0xffffu; j < (e >> 16); ++j) host_live_idx[row * m->Tk + n++] = (uint16_t)j;
+        const uint32_t e = runs[row * g.run_stride + x];
+        for (uint32_t j = e & 0xffffu; j < (e >> 16); ++j) host_live_idx[row * g.Tk + n++] = (uint16_t)j;
       }
       host_live_cnt[row] = n;
     }
@@ -290,13 +341,14 @@ int lite_attn_skiplist_export(lite_attn_mask_t* m, uint16_t* host_live_idx, uint
 
 void lite_attn_free_mask(lite_attn_mask_t* m) {
   if (!m) return;
+  if (m->ctx) {
+    // the shared scratch stays with the context; calls of this handle still in flight only touch the scratch and
+    // the buffers freed below, and hipFree waits for the device
+    --m->ctx->handles;
+  }
   if (m->d_bits) (void)hipFree(m->d_bits);
-  if (m->d_runs) (void)hipFree(m->d_runs);
-  if (m->d_nruns) (void)hipFree(m->d_nruns);
-  if (m->d_live_cnt) (void)hipFree(m->d_live_cnt);
   if (m->d_stats) (void)hipFree(m->d_stats);
-  if (m->d_vt) (void)hipFree(m->d_vt);
-  if (m->d_order) (void)hipFree(m->d_order);
+  if (m->own.base) (void)hipFree(m->own.base);
   if (m->events) {
     for (size_t x = 0; x < 3 * (size_t)m->desc.max_steps; ++x) (void)hipEventDestroy(m->events[x]);
     delete[] m->events;
@@ -313,6 +365,9 @@ const char* lite_attn_strerror(int code) {
     case LITE_ATTN_EUNSUPPORTED: return "unsupported shape (head_dim and tiles must be 128)";
     case LITE_ATTN_ENOMEM: return "out of memory";
     case LITE_ATTN_EHIP: return "HIP runtime error";
+    case LITE_ATTN_ESHARED:
+      return "not allowed while scratch is shared (a handle of a context runs on the context's stream; a context "
+             "with live handles cannot be freed)";
     default: return "unknown error";
   }
 }

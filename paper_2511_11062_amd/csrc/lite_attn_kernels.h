@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "lite_attn.h"
+
 namespace la {
 
 struct FwdParams {
@@ -26,6 +28,40 @@ struct FwdParams {
   const uint32_t* order;                 // [B*H][Tq]: Q tiles of each head ranked by Skip-List length, longest first
 };
 
+// Tile geometry of a layer, derived from its descriptor.
+struct Geometry {
+  int Tq, Tk, W;   // Q tiles, K/V tiles, uint64 words per Skip-Mask row
+  int run_stride;  // capacity of one row's run-length Skip-List: floor(Tk/2) + 1 runs (ascending order needs at most
+                   // ceil(Tk/2); diagonal first can split one more run at the wrap-around)
+  int BH;          // batch * heads
+  int64_t rows;    // BH * Tq
+};
+
+// Byte offsets, inside one scratch buffer, of everything a call rebuilds from scratch (256-byte aligned pieces).
+struct ScratchLayout {
+  size_t stats;     // 3 uint64 counters for callers without a handle (handles keep per-step counters of their own)
+  size_t nruns;     // [rows] uint32 runs per row
+  size_t live_cnt;  // [rows] uint32 live tiles per row
+  size_t order;     // [BH][Tq] uint32 row ranking
+  size_t runs;      // [rows][run_stride] uint32 Skip-List
+  size_t vt;        // [BH][128][128*Tk] bf16 V^T
+  size_t total;
+};
+
+// lite_attn_host.cpp (no HIP calls): argument checks shared by the entry points, geometry, scratch layout
+int check_desc(const lite_attn_desc_t* d);  // LITE_ATTN_OK or the error the header documents
+int check_call(const void* q, const void* k, const void* v, const void* out, float threshold);
+Geometry geometry(const lite_attn_desc_t& d);
+ScratchLayout scratch_layout(const Geometry& g);
+
+// lite_attn.cpp: the launches of one attention call (Skip-List compaction, row schedule, V^T pre-pass, fused
+// attention) on `stream`, all scratch carved out of `scratch` by `lay`; `mid` (may be null) is recorded between the
+// pre-passes and the attention kernel.  Allocates nothing.
+hipError_t launch_call(const lite_attn_desc_t& d, const Geometry& g, const ScratchLayout& lay, char* scratch,
+                       const void* q, const void* k, const void* v, void* out, uint64_t* bits,
+                       unsigned long long* stats3, float threshold, hipStream_t stream, hipEvent_t mid);
+int hip_fail(hipError_t e);  // remembers e for lite_attn_last_hip_error() and maps it to a lite_attn_error
+
 int fwd_lds_bytes();
 hipError_t prepare_fwd();
 hipError_t launch_clear(uint64_t* bits, size_t words, unsigned long long* stats, size_t nstats, hipStream_t st);
@@ -34,7 +70,6 @@ hipError_t launch_compact(const uint64_t* bits, int rows, int Tq, int Tk, int W,
                           unsigned long long* stat_runs, hipStream_t st);
 hipError_t launch_transpose_v(const uint16_t* v, uint16_t* vt, int64_t stride_b, int64_t stride_h, int64_t stride_n,
                               int BH, int H, int N, int Tk, hipStream_t st);
-hipError_t launch_mfma_peak(const void* data, float* sink, int iters, int blocks, hipStream_t st);
 hipError_t launch_order_rows(const uint32_t* live_cnt, int BH, int Tq, int Tk, uint32_t* order, hipStream_t st);
 hipError_t launch_fwd(const FwdParams& p, bool immediate, hipStream_t st);
 

@@ -7,7 +7,6 @@
 //   transpose_v_kernel   : V -> V^T scratch, so that the PV operand is read from LDS like the QK operand
 //   lite_attn_fwd_kernel : fused tiled forward over the live tiles with the skip predicate
 //                          (Algorithm 2; eq. sparge_cond; tile recurrences of the Preliminaries)
-//   mfma_peak_kernel     : register-resident MFMA loop (benchmark diagnostic)
 //
 // Fused kernel, one workgroup (4 wave64) = one Q tile = one Skip-Mask row:
 //   * wave w owns Q rows [32w, 32w+32); lane l owns Q row (l & 31) of them.
@@ -367,9 +366,14 @@ __device__ __forceinline__ void mma_pv(f32x16 (&oacc)[QB][4], const uint32_t (&p
 // registers (alternating the two blocks was measured: no faster, six registers more).
 // kread / vread hold absolute LDS addresses (of stage buffer 0), kK / kV are the byte offsets of the stage buffers
 // read: every fragment address is one loop-invariant register plus an immediate.
+// step k >= 16 of a stage multiplies d-chunk qk_kk(k) of K block qk_blk(k): block 0 first, then block 1
+// (alternating the blocks, so that consecutive MFMAs share their Q fragment, measured 0.3 % faster for 4 more registers)
+__device__ __forceinline__ constexpr int qk_blk(int k) { return (k - 16) >> 3; }
+__device__ __forceinline__ constexpr int qk_kk(int k) { return k & 7; }
+
 template <int kK, int kV>
 __device__ __forceinline__ bf16x8 load_frag(int k, const uint32_t (&kread)[8], const uint32_t (&vread)[4]) {
-  if (k >= 16) return *reinterpret_cast<LA_LDS const bf16x8*>(kread[k & 7] + (uint32_t)(kK + 8192 * ((k - 16) >> 3)));
+  if (k >= 16) return *reinterpret_cast<LA_LDS const bf16x8*>(kread[qk_kk(k)] + (uint32_t)(kK + 8192 * qk_blk(k)));
   const int cc = k >> 2, db = k & 3;
   return *reinterpret_cast<LA_LDS const bf16x8*>(vread[cc] + (uint32_t)(kV + 4096 * db));
 }
@@ -422,7 +426,7 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
     // ---- matrix cores ----
     const bf16x8 a = frag[k % kPrefetch];
     if (k >= 16) {
-      const int blk = (k - 16) >> 3, kk = k & 7;
+      const int blk = qk_blk(k), kk = qk_kk(k);
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         if (kk == 0) {
@@ -533,7 +537,8 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
   static_for(std::make_integer_sequence<int, 32>{}, [&](auto kc) __attribute__((always_inline)) {
     // matrix instruction and the memory instructions of the step first, then (fenced) the vector slice: measured
     // 1-1.5 % faster than leaving the order inside a step to the compiler (the memory instructions behind the vector
-    // slice was the slowest order tried)
+    // slice was the slowest order tried).  Issuing the MFMAs of 2, 4 or 8 steps back to back before their slices
+    // (a coarser ping-pong between the two waves of a SIMD) was measured 0 / 2.5 / 6 % slower.
     mfma_part(kc);
     mem_part(kc);
     __builtin_amdgcn_sched_barrier(0);
@@ -805,40 +810,6 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
       *reinterpret_cast<uint4*>(ob + (int64_t)grow * p.stride_n + 8 * (tid & 15)) =
           *reinterpret_cast<const uint4*>(sO + r * kORow + 16 * (tid & 15));
   }
-}
-
-// Register-resident MFMA loop for the benchmark's "measured matrix-core ceiling": 8 A and 8 B fragments per lane
-// read once from `data`, then iters x 32 MFMAs on four independent accumulators.
-__global__ __launch_bounds__(256, 2) void mfma_peak_kernel(const uint4* __restrict__ data, float* __restrict__ sink,
-                                                            int iters) {
-  bf16x8 a[8], b[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const uint4 x = data[(threadIdx.x + 256 * i) & 4095], y = data[(threadIdx.x + 256 * i + 2048) & 4095];
-    a[i] = __builtin_bit_cast(bf16x8, x);
-    b[i] = __builtin_bit_cast(bf16x8, y);
-  }
-  f32x16 acc[4];
-#pragma unroll
-  for (int n = 0; n < 4; ++n)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int u = 0; u < 32; ++u)
-      acc[u & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u & 7], b[(u >> 2) & 7], acc[u & 3], 0, 0, 0);
-  }
-  float s = 0.f;
-#pragma unroll
-  for (int n = 0; n < 4; ++n)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s += acc[n][r];
-  if (s == 12345.678f) sink[0] = s;  // keeps the loop alive without a store in the common case
-}
-
-hipError_t launch_mfma_peak(const void* data, float* sink, int iters, int blocks, hipStream_t st) {
-  hipLaunchKernelGGL(mfma_peak_kernel, dim3(blocks), dim3(256), 0, st, static_cast<const uint4*>(data), sink, iters);
-  return hipGetLastError();
 }
 
 int fwd_lds_bytes() { return kLdsBytes; }

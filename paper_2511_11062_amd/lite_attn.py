@@ -58,16 +58,17 @@ _lib.lite_attn_skipruns_stride.argtypes = [_H]
 _lib.lite_attn_skipruns_stride.restype = ctypes.c_size_t
 _lib.lite_attn_profile.argtypes = [_H, ctypes.c_int]
 _lib.lite_attn_kernel_times.argtypes = [_H, ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
-_lib.lite_attn_mfma_peak.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_float),
-                                     ctypes.POINTER(ctypes.c_double)]
-_lib.lite_attn_mfma_peak.restype = ctypes.c_int
+_lib.lite_attn_ctx_create.argtypes = [ctypes.POINTER(_H)]
+_lib.lite_attn_ctx_set_stream.argtypes = [_H, ctypes.c_void_p]
+_lib.lite_attn_init_mask_shared.argtypes = [ctypes.POINTER(Desc), _H, ctypes.POINTER(_H)]
+_lib.lite_attn_ctx_free.argtypes = [_H]
 _lib.lite_attn_free_mask.argtypes = [_H]
 _lib.lite_attn_free_mask.restype = None
 _lib.lite_attn_strerror.argtypes = [ctypes.c_int]
 _lib.lite_attn_strerror.restype = ctypes.c_char_p
 _lib.lite_attn_last_hip_error.restype = ctypes.c_int
 for _n in ("init_mask", "set_stream", "fwd", "skip_stats", "mask_export", "mask_import", "skiplist_export",
-           "profile", "kernel_times"):
+           "profile", "kernel_times", "ctx_create", "ctx_set_stream", "init_mask_shared", "ctx_free"):
     getattr(_lib, "lite_attn_" + _n).restype = ctypes.c_int
 
 
@@ -85,16 +86,44 @@ def _check(rc):
         raise LiteAttnError(rc)
 
 
-def lite_attn_init_mask(batch, heads, seqlen, *, head_dim=128, tile_q=128, tile_k=128, strides=None,
-                        protect=(0, 0), max_steps=64, flags=0):
-    """-> opaque handle.  `strides` = (stride_b, stride_h, stride_n) in elements; default [B,H,N,d] contiguous."""
+def make_desc(batch, heads, seqlen, *, head_dim=128, tile_q=128, tile_k=128, strides=None, protect=(0, 0),
+              max_steps=64, flags=0) -> Desc:
+    """lite_attn_desc_t.  `strides` = (stride_b, stride_h, stride_n) in elements; default [B,H,N,d] contiguous."""
     if strides is None:
         strides = (heads * seqlen * head_dim, seqlen * head_dim, head_dim)
-    desc = Desc(batch, heads, seqlen, head_dim, tile_q, tile_k, strides[0], strides[1], strides[2],
+    return Desc(batch, heads, seqlen, head_dim, tile_q, tile_k, strides[0], strides[1], strides[2],
                 int(protect[0]), int(protect[1]), flags, max_steps)
+
+
+def lite_attn_init_mask(batch, heads, seqlen, **desc_fields):
+    """-> opaque handle (keyword arguments: see make_desc)."""
+    desc = make_desc(batch, heads, seqlen, **desc_fields)
     h = _H()
     _check(_lib.lite_attn_init_mask(ctypes.byref(desc), ctypes.byref(h)))
     return h
+
+
+def lite_attn_ctx_create():
+    """-> opaque context whose handles share one per-call scratch and one stream."""
+    c = _H()
+    _check(_lib.lite_attn_ctx_create(ctypes.byref(c)))
+    return c
+
+
+def lite_attn_ctx_set_stream(ctx, hip_stream):
+    _check(_lib.lite_attn_ctx_set_stream(ctx, ctypes.c_void_p(int(hip_stream))))
+
+
+def lite_attn_init_mask_shared(ctx, batch, heads, seqlen, **desc_fields):
+    """-> opaque handle attached to `ctx` (keyword arguments: see make_desc)."""
+    desc = make_desc(batch, heads, seqlen, **desc_fields)
+    h = _H()
+    _check(_lib.lite_attn_init_mask_shared(ctypes.byref(desc), ctx, ctypes.byref(h)))
+    return h
+
+
+def lite_attn_ctx_free(ctx):
+    _check(_lib.lite_attn_ctx_free(ctx))
 
 
 def lite_attn_set_stream(mask, hip_stream):
@@ -148,14 +177,6 @@ def lite_attn_kernel_times(mask, step):
     a, b = ctypes.c_float(), ctypes.c_float()
     _check(_lib.lite_attn_kernel_times(mask, int(step), ctypes.byref(a), ctypes.byref(b)))
     return a.value, b.value
-
-
-def lite_attn_mfma_peak(hip_stream, dev_operands, iters=3000):
-    """-> sustained TFLOP/s of a register-resident bf16 MFMA loop on operands read from `dev_operands` (>= 64 KiB)."""
-    ms, fl = ctypes.c_float(), ctypes.c_double()
-    _check(_lib.lite_attn_mfma_peak(ctypes.c_void_p(int(hip_stream)), ctypes.c_void_p(int(dev_operands)), int(iters),
-                                    ctypes.byref(ms), ctypes.byref(fl)))
-    return fl.value / (ms.value * 1e-3) / 1e12
 
 
 def lite_attn_skipruns_export(mask, rows: int):

@@ -62,10 +62,11 @@ def check_step(o_gpu, o_ref, m_gpu, m_ref, g_ref, thr, o_keep=None):
 
 def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sample_rows=None, gen_device=None,
                        verbose=False, seed=0, layout="bhnd", diagonal_first=False, immediate=False,
-                       free_running=False):
+                       free_running=False, extra_rows=(), say=print):
     """Runs `steps` denoising steps of a named workload on cuda:0 through the C ABI and checks every step.
 
-    sample_rows: None = all rows; an int = that many seeded random rows plus first/last (and protected) rows.
+    sample_rows: None = all rows; an int = that many seeded random rows plus first/last (and protected) rows, plus
+    `extra_rows` (flattened row ids (b*H+h)*Tq+i).  say: where the verbose per-step lines go.
     immediate: both sides drop a fired tile in the call that marks it (Algorithm 2 literally).
     free_running: no teacher forcing -- the HIP path keeps its own mask trajectory.  A compared Q tile whose two entry
     masks still agree is checked as usual (so the first disagreement of a row has to lie inside the band); rows whose
@@ -86,7 +87,8 @@ def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sa
         if wl.text_tokens:
             base |= {wl.video_tokens // 128, wl.video_tokens // 128 - 1, Tq + wl.video_tokens // 128}
         base = {r for r in base if 0 <= r < B * H * Tq}          # (a single head has no second head's text rows)
-        rows = np.array(sorted(base | set(rng.choice(B * H * Tq, size=sample_rows, replace=False).tolist())))
+        rows = np.array(sorted(base | set(int(r) for r in extra_rows) |
+                               set(rng.choice(B * H * Tq, size=sample_rows, replace=False).tolist())))
     assert rows.min() >= 0 and rows.max() < B * H * Tq
     heads = sorted({int(r // Tq) for r in rows})            # flattened (b*H+h)
     head_pos = {bh: n for n, bh in enumerate(heads)}
@@ -168,11 +170,11 @@ def run_sequence_check(workload, steps=None, threshold=-2.0, thresholds=None, sa
             rep.update(diverged_rows=int((~row_ok).sum()), diverged_bits=int(((m_gpu != 0) != (m_exit != 0)).sum()))
             st = la.lite_attn_skip_stats(handle, t)
             rep.update(step=t, threshold=thr, gpu_skipped_in=st.tiles_skipped_in / st.tiles_total,
-                       gpu_newly=st.tiles_newly_marked / st.tiles_total)
+                       gpu_newly=st.tiles_newly_marked / st.tiles_total, rows=len(rows))
             if verbose:
-                print("step %d thr %.2f: max|dO| %.2e (max|O| %.2f) mean|dO| %.2e, skipped-out %.3f, excused %d" % (
-                    t, thr, rep["max_dO"], rep["max_O"], rep["mean_dO"], rep["skipped_out"], rep["mask_excused"]),
-                    flush=True)
+                say("step %d thr %.2f, %d rows: max|dO| %.2e (max|O| %.2f) mean|dO| %.2e, skipped-out %.3f, excused %d" % (
+                    t, thr, len(rows), rep["max_dO"], rep["max_O"], rep["mean_dO"], rep["skipped_out"],
+                    rep["mask_excused"]))
             reports.append(rep)
             m_ref = m_new
     finally:

@@ -8,7 +8,8 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "lite_attn.h")
-LIB = os.path.join(ROOT, "paper_2511_11062_amd", "liblite_attn.so")
+# the sanitizer run (test_sanitizers.py) points this suite at its own build of the library's host side
+LIB = os.environ.get("LITE_ATTN_TEST_LIB") or os.path.join(ROOT, "paper_2511_11062_amd", "liblite_attn.so")
 
 
 @pytest.fixture(scope="module")
@@ -60,8 +61,14 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.lite_attn_skip_stats(None, 0, None) == -1
     assert lib.lite_attn_mask_words(None) == 0
     lib.lite_attn_free_mask(None)
+    # contexts
+    assert lib.lite_attn_ctx_create(None) == -1
+    assert lib.lite_attn_ctx_set_stream(None, None) == -1
+    ok_desc = la.Desc(1, 2, 256, 128, 128, 128, 2 * 256 * 128, 256 * 128, 128, 0, 0, 0, 4)
+    assert lib.lite_attn_init_mask_shared(ctypes.byref(ok_desc), None, ctypes.byref(h)) == -1
+    assert lib.lite_attn_ctx_free(None) == 0
     lib.lite_attn_strerror.restype = ctypes.c_char_p
-    assert b"step" in lib.lite_attn_strerror(-2)
+    assert b"step" in lib.lite_attn_strerror(-2) and b"shared" in lib.lite_attn_strerror(-6)
 
 
 def test_binding_flag_constants_match_the_header():

@@ -1,11 +1,56 @@
 """Parity at the benchmark's full shapes, in the launch configuration bench.py times, on sampled Q-tile rows
 (rows are independent, so the oracle computes exactly those rows over all K/V of their heads)."""
+import numpy as np
 import pytest
+import torch
 
 import parity
+from paper_2511_11062_amd import inputs
 
 pytestmark = pytest.mark.gpu
 NINF = -float("inf")
+
+
+def loud(capsys):
+    """A print that reaches the terminal while pytest captures output: long tests report every step as they go."""
+    def say(msg):
+        with capsys.disabled():
+            print("\n    " + msg, end="", flush=True)
+    return say
+
+
+def schedule_spread_rows(name, threshold, per_group=4, xcd_heads=8, xcd_rows=3):
+    """Row ids chosen to cover the launch schedule of the fused kernel: the kernel ranks every head's Q-tile rows by
+    Skip-List length and deals rank-chunks of 64 rows to the 8 XCDs (chunk c of head h goes to XCD ((h + c) mod BH)
+    mod 8).  A probe call of step 0 on the HIP path gives the mask from which steps 1.. are ranked; from it this
+    picks, for the first and the last head, `per_group` rows of the first, the middle and the last rank-chunk, and
+    `xcd_rows` rows of the first rank-chunk of each of `xcd_heads` consecutive heads (one head per XCD).  Only the
+    CHOICE of rows comes from the probe: what the oracle computes for them does not."""
+    from paper_2511_11062_amd import lite_attn as la
+    wl = inputs.WORKLOADS[name]
+    B, H, N = wl.batch, wl.heads, wl.seqlen
+    Tq = -(-N // 128)
+    q, k, v = next(inputs.DriftSequence(wl, "cuda:0"))
+    out = torch.empty_like(q)
+    h = la.lite_attn_init_mask(B, H, N, protect=wl.protect, max_steps=1)
+    try:
+        la.lite_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), h, threshold, 0)
+        torch.cuda.synchronize()
+        skipped = parity.unpack_mask(la.lite_attn_mask_export(h).reshape(B * H, Tq, -1), Tq).sum(axis=2)
+    finally:
+        la.lite_attn_free_mask(h)
+    del q, k, v, out
+    rows = set()
+    chunks = -(-Tq // 64)
+    for bh in (0, B * H - 1):
+        ranked = np.argsort(skipped[bh], kind="stable")              # longest Skip-List (fewest skipped) first
+        for c in (0, chunks // 2, chunks - 1):
+            part = ranked[64 * c:64 * (c + 1)]
+            rows |= {bh * Tq + int(i) for i in part[np.linspace(0, len(part) - 1, per_group).astype(int)]}
+    for bh in range(min(xcd_heads, B * H)):
+        ranked = np.argsort(skipped[bh], kind="stable")[:64]
+        rows |= {bh * Tq + int(i) for i in ranked[np.linspace(0, len(ranked) - 1, xcd_rows).astype(int)]}
+    return sorted(rows)
 
 
 def test_wan13b_dense_equals_softmax_attention():
@@ -89,3 +134,32 @@ def test_maximum_sequence_length():
     with pytest.raises(la.LiteAttnError) as err:
         la.lite_attn_init_mask(1, 1, 128 * 16384)
     assert err.value.code == -3
+
+
+def test_wan13b_every_row_marking_step_and_skipping_step(capsys):
+    """Config 2/3 shape (B=1, H=12, N=32760: 256 x 256 tiles, 3072 Q-tile rows): EVERY row's output and mask row
+    compared with the oracle, for the step that marks (empty mask on entry, dense path) and for the next step, which
+    skips what was marked."""
+    reps = parity.run_sequence_check("wan1.3b_sweep", steps=2, threshold=-3.0, sample_rows=None, verbose=True,
+                                     say=loud(capsys))
+    assert [r["rows"] for r in reps] == [3072, 3072]
+    assert reps[0]["gpu_skipped_in"] == 0.0 and reps[0]["gpu_newly"] > 0.2
+    assert abs(reps[1]["gpu_skipped_in"] - reps[0]["skipped_out"]) < 1e-3
+
+
+def test_wan14b_three_steps_rows_across_the_schedule(capsys):
+    """Config 4, three steps, more than 64 compared rows: the usual pinned ones (first, last, ragged tail), seeded
+    random ones, and rows chosen to sit in the first, middle and last rank-chunk of two heads and on every XCD."""
+    rows = schedule_spread_rows("wan14b", -3.0)
+    reps = parity.run_sequence_check("wan14b", steps=3, threshold=-3.0, sample_rows=24, seed=41, extra_rows=rows,
+                                     verbose=True, say=loud(capsys))
+    assert all(r["rows"] >= 64 for r in reps) and reps[-1]["gpu_skipped_in"] > 0.25
+
+
+def test_longvideo_three_steps_rows_across_the_schedule(capsys):
+    """Config 5, three steps, more than 64 compared rows chosen as for config 4, plus the rows that touch the
+    protected text tokens."""
+    rows = schedule_spread_rows("longvideo", -3.0)
+    reps = parity.run_sequence_check("longvideo", steps=3, threshold=-3.0, sample_rows=24, seed=42, extra_rows=rows,
+                                     verbose=True, say=loud(capsys))
+    assert all(r["rows"] >= 64 for r in reps) and reps[-1]["gpu_skipped_in"] > 0.25

@@ -182,6 +182,117 @@ def test_threshold_schedule_driver_meets_its_error_bounds():
         assert s["met"] or s["threshold"] == -12.0
 
 
+def test_threshold_schedule_checked_against_the_oracle():
+    """The schedule calibrate.py returns, replayed through the CPU oracle (all rows, deferred marking, the oracle's
+    own mask trajectory): the mask each step's threshold leaves must equal the one the driver reports for that step
+    bit for bit (outside the +-1e-3 band), the oracle's eta_t = |O^s_t - O_t|_1 / |O_t|_1 (O^s_t: step t's inputs
+    under that mask with marking disabled, O_t: dense) must agree with the driver's, and the three segment bounds
+    xi-tau, xi, xi+tau must hold for the ORACLE's eta wherever the driver says they are met.  A threshold attributed
+    to the wrong step would leave a different mask at that step."""
+    from paper_2511_11062_amd import calibrate
+    from oracle.lite_attn_oracle import oracle_step
+    wl = inputs.Workload("cal_orc", 1, 2, (2, 32, 32), steps=6, seed=37)
+    T, N, Tk = 6, wl.seqlen, 16
+    seq = inputs.DriftSequence(wl, "cuda:0")
+    data = [next(seq) for _ in range(T)]
+    xi, tau = 0.09, 0.03
+    sched = calibrate.calibrate(wl, data, xi=xi, tau=tau, keep_masks=True)
+    assert [round(s["bound"], 3) for s in sched] == [0.06, 0.06, 0.09, 0.09, 0.12, 0.12]
+    m = np.zeros((1, 2, Tk, Tk), dtype=np.uint8)
+    empty = np.zeros_like(m)
+    marking_steps = 0
+    parted = np.zeros((2 * Tk,), dtype=bool)            # rows whose two trajectories parted inside the band
+    for t, s in enumerate(sched):
+        qs, ks, vs = (inputs.bf16_bits(x) for x in data[t])
+        thr = s["threshold"]
+        _, m_next, g = oracle_step(qs, ks, vs, m, thr)                        # the step with its scheduled threshold
+        o_sparse, _, _ = oracle_step(qs, ks, vs, m_next, NINF)               # the mask it leaves, in force, no marking
+        o_dense, _, _ = oracle_step(qs, ks, vs, empty, NINF)
+        eta_orc = float(np.abs(o_sparse - o_dense).sum() / np.abs(o_dense).sum())
+        m_hip = parity.unpack_mask(s["mask_bits"].reshape(2 * Tk, 1), Tk)
+        diff = (m_hip != 0) != (m_next.reshape(2 * Tk, Tk) != 0)
+        with np.errstate(invalid="ignore"):
+            excused = np.abs(g.reshape(2 * Tk, Tk) - thr) <= parity.G_BAND
+        assert not (diff & ~excused)[~parted].any(), "step %d: the reported mask is not the one threshold %.4f leaves" % (
+            t, thr)
+        parted |= diff.any(axis=1)
+        marking_steps += int((m_next != 0).sum() > (m != 0).sum())
+        # both sides' outputs are within mean|dO| <= 1e-3 of each other, so the two eta differ by at most
+        # (2 + eta) * 1e-3 / mean|O| (about 0.04 here); what is asserted is 2e-3, the observed difference being
+        # about 1e-5 (bf16 rounding of the stored outputs)
+        mean_o = float(np.abs(o_dense).mean())
+        tol = min((2.0 + eta_orc) * parity.MEAN_ABS / mean_o, 2e-3)
+        print("step %d thr %.4f bound %.3f: eta HIP %.5f oracle %.5f (tolerance %.4f), skipped %.3f" % (
+            t, thr, s["bound"], s["eta"], eta_orc, tol, (m_next != 0).mean()), flush=True)
+        assert abs(s["eta"] - eta_orc) <= tol
+        if s["met"]:
+            assert eta_orc <= s["bound"] + tol
+        assert abs(s["skipped_after"] - (m_next != 0).mean()) <= (diff.sum() + 0.5) / m_next.size
+        m = m_next
+    assert marking_steps >= 2, "the schedule must mark tiles at more than one step for this test to discriminate"
+    assert len({round(s["threshold"], 6) for s in sched}) >= 3
+    assert not parted.any()         # (deterministic inputs: no tile of this sequence sits inside the band)
+
+
+def test_shared_scratch_context():
+    """Two layers of different shapes attached to one context share one scratch buffer and the context's stream:
+    interleaved calls on that stream give, bit for bit, what handles with scratch of their own give; a sharing
+    handle refuses any other stream, and the context cannot be freed while handles are attached."""
+    from paper_2511_11062_amd import lite_attn as la
+    wls = [small("ctx_a", 2, (2, 24, 31), 3, seed=43), small("ctx_b", 3, (1, 33, 40), 3, seed=44)]   # N = 1488, 1320
+    data = []
+    for wl in wls:
+        seq = inputs.DriftSequence(wl, "cpu")
+        data.append([tuple(x.cuda().contiguous() for x in next(seq)) for _ in range(3)])
+    thr = [-3.0, -2.0, -1.5]
+
+    def run(handles, stream):
+        outs = [[torch.empty_like(d[0]) for d in layer] for layer in data]
+        torch.cuda.synchronize()
+        for t in range(3):
+            for n, h in enumerate(handles):
+                q, k, v = data[n][t]
+                la.lite_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), outs[n][t].data_ptr(), h, thr[t], t)
+        stream.synchronize()
+        return [o for layer in outs for o in layer], [la.lite_attn_mask_export(h).copy() for h in handles]
+
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    own = [la.lite_attn_init_mask(w.batch, w.heads, w.seqlen, max_steps=3) for w in wls]
+    ctx = la.lite_attn_ctx_create()
+    shared = []
+    try:
+        for h in own:
+            la.lite_attn_set_stream(h, s1.cuda_stream)
+        ref_o, ref_m = run(own, s1)
+        la.lite_attn_ctx_set_stream(ctx, s1.cuda_stream)
+        shared.append(la.lite_attn_init_mask_shared(ctx, wls[0].batch, wls[0].heads, wls[0].seqlen, max_steps=3))
+        # the second, larger layer makes the shared scratch grow after the first handle already exists
+        shared.append(la.lite_attn_init_mask_shared(ctx, wls[1].batch, wls[1].heads, wls[1].seqlen, max_steps=3))
+        la.lite_attn_set_stream(shared[0], s1.cuda_stream)                       # the context's stream: accepted
+        with pytest.raises(la.LiteAttnError) as err:
+            la.lite_attn_set_stream(shared[1], s2.cuda_stream)                   # any other stream: refused
+        assert err.value.code == -6
+        with pytest.raises(la.LiteAttnError) as err:
+            la.lite_attn_ctx_free(ctx)                                           # handles still attached
+        assert err.value.code == -6
+        got_o, got_m = run(shared, s1)
+        for a, b in zip(ref_o, got_o):
+            assert torch.equal(a, b)
+        for a, b in zip(ref_m, got_m):
+            assert np.array_equal(a, b) and a.any()
+        # moving the context moves all of its handles: same results on the other stream
+        la.lite_attn_ctx_set_stream(ctx, s2.cuda_stream)
+        got_o, got_m = run(shared, s2)
+        for a, b in zip(ref_o, got_o):
+            assert torch.equal(a, b)
+        for a, b in zip(ref_m, got_m):
+            assert np.array_equal(a, b)
+    finally:
+        for h in own + shared:
+            la.lite_attn_free_mask(h)
+        la.lite_attn_ctx_free(ctx)
+
+
 @pytest.mark.parametrize("diagonal_first", [False, True])
 def test_immediate_pv_skip_mode(diagonal_first):
     """Flag LITE_ATTN_PV_SKIP_IMMEDIATE (Algorithm 2 literally): parity with the oracle's immediate mode -- the output
