@@ -40,8 +40,9 @@ typedef enum {
                                   2097024), or one head's K/V spanning 4 GiB or more ((seqlen+128)*stride_n*2 bytes) */
   LITE_ATTN_ENOMEM = -4,       /* host or device allocation failed */
   LITE_ATTN_EHIP = -5,         /* a HIP runtime call failed; lite_attn_last_hip_error() has its code */
-  LITE_ATTN_ESHARED = -6       /* refused because scratch is shared: lite_attn_set_stream on a handle of a context with
+  LITE_ATTN_ESHARED = -6,      /* refused because scratch is shared: lite_attn_set_stream on a handle of a context with
                                   any stream but the context's; lite_attn_ctx_free while handles are attached */
+  LITE_ATTN_ESCRATCH = -7      /* lite_attn_fwd_static: the shape needs more than LITE_ATTN_STATIC_SCRATCH_BYTES */
 } lite_attn_error;
 
 /* desc.flags.  The skip predicate compares a tile with the running row maximum over the tiles visited BEFORE it, so
@@ -130,6 +131,29 @@ int lite_attn_ctx_free(lite_attn_ctx_t* ctx);
    replayed step keep adding up unless the replay includes step 0, which clears them. */
 int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_attn_mask_t* skip_mask,
                   float threshold, int step);
+
+/* The same attention call for callers that cannot allocate device memory at all -- code running under HIP graph
+   capture, serving loops and harnesses that forbid hipMalloc -- and therefore cannot create a handle.  It allocates
+   nothing and frees nothing: no hipMalloc, no hipFree, no allocating library routine.  Everything the other entry
+   points keep in allocated device memory besides the Skip-Mask (Skip-List, row schedule, V^T, the call's counters)
+   lives in ONE static device array of LITE_ATTN_STATIC_SCRATCH_BYTES that the library's code object brings along on
+   every GPU it is loaded on and holds until the process ends.
+     q, k, v, out, threshold   as for lite_attn_fwd
+     desc            shape, strides, protected range and flags of the layer, as for lite_attn_init_mask (max_steps
+                     must be >= 1 and is otherwise unused)
+     dev_skip_mask   DEVICE pointer, 8-byte aligned, to the layer's Skip-Mask: B*H*Tq*ceil(Tk/64) uint64 words in the
+                     handle's layout (bit j%64 of word j/64 of row (b*H+h)*Tq+i set = tile (i,j) skipped).  Input and
+                     output: the caller owns it, keeps it between timesteps, and zeroes it to start a new trajectory
+     hip_stream      hipStream_t on which the call's kernels are enqueued (asynchronous)
+   A shape whose scratch (about the size of V plus 2*Tk+12 bytes per Q-tile row) exceeds the array is refused with
+   LITE_ATTN_ESCRATCH before anything is launched: B*H*ceil(N/128) up to about 4000, e.g. the 12-head N=32760
+   layer; the larger benchmark shapes need a handle.  The first call on a GPU looks up the array's address there.
+   Every call on a GPU uses that GPU's one array, which keeps the previous call's contents (what has to start at
+   zero is cleared by the call itself): calls that overlap in time on one GPU -- two streams, two threads -- race;
+   calls on one stream are safe. */
+#define LITE_ATTN_STATIC_SCRATCH_BYTES (128u << 20)
+int lite_attn_fwd_static(const void* q, const void* k, const void* v, void* out, const lite_attn_desc_t* desc,
+                         uint64_t* dev_skip_mask, float threshold, void* hip_stream);
 
 /* Statistics of one completed step (paper's sparsity = skipped fraction of tiles, Experiments "Metrics").
    Synchronises the handle's stream. */

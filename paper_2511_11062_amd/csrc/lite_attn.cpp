@@ -368,6 +368,7 @@ const char* lite_attn_strerror(int code) {
     case LITE_ATTN_ESHARED:
       return "not allowed while scratch is shared (a handle of a context runs on the context's stream; a context "
              "with live handles cannot be freed)";
+    case LITE_ATTN_ESCRATCH: return "the shape needs more scratch than the static device array holds";
     default: return "unknown error";
   }
 }

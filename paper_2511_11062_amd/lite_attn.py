@@ -58,6 +58,9 @@ _lib.lite_attn_skipruns_stride.argtypes = [_H]
 _lib.lite_attn_skipruns_stride.restype = ctypes.c_size_t
 _lib.lite_attn_profile.argtypes = [_H, ctypes.c_int]
 _lib.lite_attn_kernel_times.argtypes = [_H, ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
+_lib.lite_attn_fwd_static.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                      ctypes.POINTER(Desc), ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p]
+_lib.lite_attn_fwd_static.restype = ctypes.c_int
 _lib.lite_attn_ctx_create.argtypes = [ctypes.POINTER(_H)]
 _lib.lite_attn_ctx_set_stream.argtypes = [_H, ctypes.c_void_p]
 _lib.lite_attn_init_mask_shared.argtypes = [ctypes.POINTER(Desc), _H, ctypes.POINTER(_H)]
@@ -135,6 +138,20 @@ def lite_attn_fwd(q, k, v, out, skip_mask, threshold, step):
     """q, k, v, out: integer device addresses (e.g. tensor.data_ptr()) of bf16 buffers."""
     _check(_lib.lite_attn_fwd(ctypes.c_void_p(int(q)), ctypes.c_void_p(int(k)), ctypes.c_void_p(int(v)),
                               ctypes.c_void_p(int(out)), skip_mask, ctypes.c_float(threshold), int(step)))
+
+
+def lite_attn_fwd_static(q, k, v, out, desc: Desc, dev_skip_mask, threshold, hip_stream):
+    """The allocation-free call.  q, k, v, out, dev_skip_mask: integer device addresses; `desc` from make_desc;
+    dev_skip_mask holds static_mask_words(desc) uint64 words owned by the caller."""
+    _check(_lib.lite_attn_fwd_static(ctypes.c_void_p(int(q)), ctypes.c_void_p(int(k)), ctypes.c_void_p(int(v)),
+                                     ctypes.c_void_p(int(out)), ctypes.byref(desc), ctypes.c_void_p(int(dev_skip_mask)),
+                                     ctypes.c_float(threshold), ctypes.c_void_p(int(hip_stream))))
+
+
+def static_mask_words(desc: Desc) -> int:
+    """uint64 words of the Skip-Mask of a layer: B*H*Tq*ceil(Tk/64)."""
+    tq, tk = -(-desc.seqlen // desc.tile_q), -(-desc.seqlen // desc.tile_k)
+    return desc.batch * desc.heads * tq * (-(-tk // 64))
 
 
 def lite_attn_skip_stats(mask, step) -> Stats:

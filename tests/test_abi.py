@@ -71,6 +71,31 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert b"step" in lib.lite_attn_strerror(-2) and b"shared" in lib.lite_attn_strerror(-6)
 
 
+def test_allocation_free_entry_point_rejects_on_the_host(lib):
+    """lite_attn_fwd_static checks its arguments and the scratch limit before it touches a device."""
+    from paper_2511_11062_amd import lite_attn as la
+    if not hasattr(lib, "lite_attn_fwd_static"):
+        pytest.skip("host-only sanitizer build: the entry point lives beside its device array")
+    f = lib.lite_attn_fwd_static
+    f.argtypes = [ctypes.c_void_p] * 4 + [ctypes.POINTER(la.Desc), ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p]
+    small = la.make_desc(1, 2, 300, max_steps=1)
+    a = 4096                                                          # never dereferenced: every case fails earlier
+    assert f(a, a, a, a, None, a, -1.0, None) == -1
+    assert f(None, a, a, a, ctypes.byref(small), a, -1.0, None) == -1
+    assert f(a, a, a, a + 8, ctypes.byref(small), a, -1.0, None) == -1           # out not 16-byte aligned
+    assert f(a, a, a, a, ctypes.byref(small), None, -1.0, None) == -1
+    assert f(a, a, a, a, ctypes.byref(small), a + 4, -1.0, None) == -1           # mask not 8-byte aligned
+    assert f(a, a, a, a, ctypes.byref(small), a, 0.5, None) == -1
+    assert f(a, a, a, a, ctypes.byref(la.make_desc(1, 2, 300, head_dim=64, strides=(2 * 300 * 64, 300 * 64, 64))), a,
+             -1.0, None) == -3
+    # the Wan-14B-like layer needs 0.77 GB of scratch: more than the static array holds
+    assert f(a, a, a, a, ctypes.byref(la.make_desc(1, 40, 75600)), a, -1.0, None) == -7
+    text = open(HEADER).read()
+    assert re.search(r"#define\s+LITE_ATTN_STATIC_SCRATCH_BYTES\s+\(128u << 20\)", text)
+    lib.lite_attn_strerror.restype = ctypes.c_char_p
+    assert b"static" in lib.lite_attn_strerror(-7)
+
+
 def test_binding_flag_constants_match_the_header():
     """The Python binding repeats the desc.flags values of the header."""
     text = open(HEADER).read()
