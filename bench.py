@@ -221,7 +221,8 @@ def main():
             r2 = run_workload(la, torch, inputs, wl2, DEFAULT_THRESHOLD[name], k2, w2, dev)
             ps = r2["per_step"]
             others.append({"workload": "%s: B=%d H=%d N=%d" % (name, wl2.batch, wl2.heads, wl2.seqlen),
-                           "threshold": DEFAULT_THRESHOLD[name], "steps": k2, "warmup": w2,
+                           "threshold": DEFAULT_THRESHOLD[name] if DEFAULT_THRESHOLD[name] > -1e30 else "-inf (disabled)",
+                           "steps": k2, "warmup": w2,
                            "ms_per_step": round(r2["wall"] / k2 * 1e3, 3),
                            "value_tflops": round(k2 * wl2.dense_flops() / r2["wall"] / 1e12, 1),
                            "attn_ms": [s_["attn_ms"] for s_ in ps], "skip_ratio": [s_["skip_ratio"] for s_ in ps],
@@ -236,7 +237,7 @@ def main():
         "config": {"workload": "%s: B=%d H=%d N=%d d=%d, %dx%dx%d latent grid%s, steps 0..%d of a drift sequence" % (
             wl.name, B, H, N, d, wl.grid[0], wl.grid[1], wl.grid[2],
             " + %d protected text tokens" % wl.text_tokens if wl.text_tokens else "", K - 1),
-            "threshold": thr, "mask_tile": "128x128",
+            "threshold": thr if thr > -1e30 else "-inf (disabled)", "mask_tile": "128x128",
             "mean_skip_ratio": round(sum(s["skip_ratio"] for s in per_step) / K, 4)},
         "dense_step": {"ms": per_step[0]["attn_ms"], "tflops": per_step[0]["attn_tflops_live"],
                        "frac_of_bf16_peak": round(per_step[0]["attn_tflops_live"] / PEAK_BF16_TFLOPS, 4),

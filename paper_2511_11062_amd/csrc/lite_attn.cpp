@@ -1,5 +1,5 @@
-// Host side of the C ABI declared in include/lite_attn.h: handles, contexts, launches (argument checks and the
-// scratch layout are in lite_attn_host.cpp).
+// Host side of the C ABI declared in include/lite_attn.h: handles, contexts, launches (argument checks and buffer
+// layouts are in lite_attn_host.cpp).
 #include "lite_attn.h"
 
 #include <hip/hip_runtime.h>
@@ -10,8 +10,8 @@
 
 #include "lite_attn_kernels.h"
 
-// Device memory that every call rebuilds from scratch (nothing in it outlives a call): the Skip-List, the row
-// schedule and V^T.  A handle either owns one or borrows its context's.
+// Device memory that every call rewrites before reading it (nothing in it outlives a call): V^T.  A handle either
+// owns one or borrows its context's.
 struct la_scratch {
   void* base = nullptr;
   size_t bytes = 0;
@@ -27,8 +27,10 @@ struct lite_attn_ctx {
 struct lite_attn_mask {
   lite_attn_desc_t desc;
   la::Geometry geo;
-  la::ScratchLayout lay;
+  la::ListLayout ll;
   uint64_t* d_bits;
+  char* d_lists;      // Skip-Lists, row ranking, per-head counters (layout ll); kept between calls
+  bool lists_valid;   // the lists describe the mask as it stands (left by the previous call's epilogue)
   unsigned long long* d_stats;  // [max_steps][3]: skipped on entry, newly marked, Skip-List runs
   la_scratch own;               // used when ctx == nullptr
   lite_attn_ctx* ctx;           // shared scratch + stream, or nullptr
@@ -50,19 +52,22 @@ int hip_fail(hipError_t e) {
   return e == hipErrorOutOfMemory ? LITE_ATTN_ENOMEM : LITE_ATTN_EHIP;
 }
 
-hipError_t launch_call(const lite_attn_desc_t& d, const Geometry& g, const ScratchLayout& lay, char* scratch,
+hipError_t launch_call(const lite_attn_desc_t& d, const Geometry& g, const ListLayout& ll, char* lists, uint16_t* vt,
                        const void* q, const void* k, const void* v, void* out, uint64_t* bits,
-                       unsigned long long* stats3, float threshold, hipStream_t stream, hipEvent_t mid) {
-  uint32_t* runs = reinterpret_cast<uint32_t*>(scratch + lay.runs);
-  uint32_t* nruns = reinterpret_cast<uint32_t*>(scratch + lay.nruns);
-  uint32_t* live_cnt = reinterpret_cast<uint32_t*>(scratch + lay.live_cnt);
-  uint32_t* order = reinterpret_cast<uint32_t*>(scratch + lay.order);
-  uint16_t* vt = reinterpret_cast<uint16_t*>(scratch + lay.vt);
-  hipError_t e = launch_compact(bits, (int)g.rows, g.Tq, g.Tk, g.W, d.flags & LITE_ATTN_ORDER_DIAGONAL_FIRST,
-                                g.run_stride, runs, nruns, live_cnt, stats3, stats3 + 2, stream);
-  if (e != hipSuccess) return e;
-  e = launch_order_rows(live_cnt, g.BH, g.Tq, g.Tk, order, stream);
-  if (e != hipSuccess) return e;
+                       unsigned long long* stats3, float threshold, bool lists_ready, bool build_next,
+                       hipStream_t stream, hipEvent_t mid) {
+  uint32_t* runs = reinterpret_cast<uint32_t*>(lists + ll.runs);
+  uint32_t* nruns = reinterpret_cast<uint32_t*>(lists + ll.nruns);
+  uint32_t* live_cnt = reinterpret_cast<uint32_t*>(lists + ll.live_cnt);
+  uint32_t* order = reinterpret_cast<uint32_t*>(lists + ll.order);
+  const int diagonal_first = (d.flags & LITE_ATTN_ORDER_DIAGONAL_FIRST) ? 1 : 0;
+  hipError_t e = hipSuccess;
+  if (!lists_ready) {
+    e = launch_compact(bits, (int)g.rows, g.Tq, g.Tk, g.W, diagonal_first, g.run_stride, runs, nruns, live_cnt, stream);
+    if (e != hipSuccess) return e;
+    e = launch_order_rows(live_cnt, g.BH, g.Tq, g.Tk, order, stream);
+    if (e != hipSuccess) return e;
+  }
   e = launch_transpose_v(static_cast<const uint16_t*>(v), vt, d.stride_b, d.stride_h, d.stride_n, g.BH, d.heads,
                          d.seqlen, g.Tk, stream);
   if (e != hipSuccess) return e;
@@ -75,12 +80,15 @@ hipError_t launch_call(const lite_attn_desc_t& d, const Geometry& g, const Scrat
   p.H = d.heads; p.N = d.seqlen; p.Tq = g.Tq; p.Tk = g.Tk; p.W = g.W;
   p.runs = runs; p.run_stride = g.run_stride; p.nruns = nruns; p.live_cnt = live_cnt;
   p.bits = bits;
-  p.stat_newly = stats3 + 1;
+  p.stat_skipped_in = stats3; p.stat_newly = stats3 + 1; p.stat_runs = stats3 + 2;
   p.thr = threshold;
   p.scale = 1.0f / std::sqrt((float)d.head_dim);
   p.protect_start = d.protect_start; p.protect_len = d.protect_len;
   p.rows_total = (int)g.rows;
   p.order = order;
+  p.build_next = build_next ? 1 : 0;
+  p.diagonal_first = diagonal_first;
+  p.done = reinterpret_cast<uint32_t*>(lists + ll.done);
   if (mid) {
     e = hipEventRecord(mid, stream);
     if (e != hipSuccess) return e;
@@ -101,7 +109,7 @@ using la::hip_fail;
   } while (0)
 
 hipStream_t stream_of(const lite_attn_mask* m) { return m->ctx ? m->ctx->stream : m->stream; }
-char* scratch_of(const lite_attn_mask* m) { return static_cast<char*>(m->ctx ? m->ctx->scratch.base : m->own.base); }
+uint16_t* vt_of(const lite_attn_mask* m) { return static_cast<uint16_t*>(m->ctx ? m->ctx->scratch.base : m->own.base); }
 
 int grow(la_scratch* s, size_t bytes) {
   if (bytes <= s->bytes) return LITE_ATTN_OK;
@@ -121,7 +129,9 @@ int init_common(const lite_attn_desc_t* desc, lite_attn_ctx* ctx, lite_attn_mask
   if (!m) return LITE_ATTN_ENOMEM;
   m->desc = *desc;
   m->geo = la::geometry(*desc);
-  m->lay = la::scratch_layout(m->geo);
+  m->ll = la::list_layout(m->geo);
+  m->d_lists = nullptr;
+  m->lists_valid = false;
   m->ctx = nullptr;
   m->stream = nullptr;
   m->next_step = 0;
@@ -131,20 +141,24 @@ int init_common(const lite_attn_desc_t* desc, lite_attn_ctx* ctx, lite_attn_mask
   m->d_bits = nullptr;
   m->d_stats = nullptr;
   const size_t words = (size_t)m->geo.rows * m->geo.W, nstats = 3 * (size_t)desc->max_steps;
+  const size_t vt = la::vt_bytes(m->geo);
   hipStream_t st = ctx ? ctx->stream : nullptr;
   rc = LITE_ATTN_OK;
   if (ctx) {
     // every call made so far through this context has to finish before its scratch may move
-    hipError_t e = m->lay.total > ctx->scratch.bytes ? hipStreamSynchronize(ctx->stream) : hipSuccess;
-    rc = e != hipSuccess ? hip_fail(e) : grow(&ctx->scratch, m->lay.total);
+    hipError_t e = vt > ctx->scratch.bytes ? hipStreamSynchronize(ctx->stream) : hipSuccess;
+    rc = e != hipSuccess ? hip_fail(e) : grow(&ctx->scratch, vt);
   } else {
-    rc = grow(&m->own, m->lay.total);
+    rc = grow(&m->own, vt);
   }
   if (rc == LITE_ATTN_OK) {
     hipError_t e = hipMalloc(&m->d_bits, sizeof(uint64_t) * words);
     if (e == hipSuccess) e = hipMalloc(&m->d_stats, sizeof(unsigned long long) * nstats);
+    if (e == hipSuccess) e = hipMalloc(&m->d_lists, m->ll.total);
     if (e == hipSuccess) e = la::prepare_fwd();
     if (e == hipSuccess) e = la::launch_clear(m->d_bits, words, m->d_stats, nstats, st);
+    if (e == hipSuccess)  // the per-head counters of finished rows (and the unused counter slot in front of them)
+      e = la::launch_clear(reinterpret_cast<uint64_t*>(m->d_lists), m->ll.nruns / sizeof(uint64_t), nullptr, 0, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) rc = hip_fail(e);
   }
@@ -223,8 +237,13 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
   hipEvent_t* ev = (m->profile && m->events) ? m->events + 3 * (size_t)step : nullptr;
   if (m->timed) m->timed[step] = ev != nullptr;
   if (ev) LA_HIP(hipEventRecord(ev[0], stream));
-  LA_HIP(la::launch_call(d, m->geo, m->lay, scratch_of(m), q, k, v, out, m->d_bits, st, threshold, stream,
-                         ev ? ev[1] : nullptr));
+  // Lists left by the previous call's epilogue are used when they still describe the mask: not at step 0 (the mask
+  // was just cleared) and not after an import.  This call's epilogue then leaves the lists of the next call.
+  const bool ready = m->lists_valid && step != 0;
+  m->lists_valid = false;
+  LA_HIP(la::launch_call(d, m->geo, m->ll, m->d_lists, vt_of(m), q, k, v, out, m->d_bits, st, threshold, ready, true,
+                         stream, ev ? ev[1] : nullptr));
+  m->lists_valid = true;
   if (ev) LA_HIP(hipEventRecord(ev[2], stream));
   m->next_step = step + 1;
   return LITE_ATTN_OK;
@@ -296,19 +315,20 @@ int lite_attn_mask_import(lite_attn_mask_t* m, const uint64_t* host_bits, size_t
   LA_HIP(hipMemcpyAsync(m->d_bits, host_bits, words * sizeof(uint64_t), hipMemcpyHostToDevice, stream_of(m)));
   LA_HIP(hipStreamSynchronize(stream_of(m)));
   m->next_step = next_step;
+  m->lists_valid = false;  // the next call rebuilds its Skip-Lists from the imported mask
   return LITE_ATTN_OK;
 }
 
 int lite_attn_skipruns_export(lite_attn_mask_t* m, uint32_t* host_runs, uint32_t* host_nruns) {
   if (!m || !host_runs || !host_nruns) return LITE_ATTN_EINVAL;
   const la::Geometry& g = m->geo;
-  char* s = scratch_of(m);
-  uint32_t* runs = reinterpret_cast<uint32_t*>(s + m->lay.runs);
-  uint32_t* nruns = reinterpret_cast<uint32_t*>(s + m->lay.nruns);
+  uint32_t* runs = reinterpret_cast<uint32_t*>(m->d_lists + m->ll.runs);
+  uint32_t* nruns = reinterpret_cast<uint32_t*>(m->d_lists + m->ll.nruns);
   hipStream_t stream = stream_of(m);
+  // (if the lists were already in place -- left by the last call's epilogue -- this writes the same values again)
   LA_HIP(la::launch_compact(m->d_bits, (int)g.rows, g.Tq, g.Tk, g.W, m->desc.flags & LITE_ATTN_ORDER_DIAGONAL_FIRST,
-                            g.run_stride, runs, nruns, reinterpret_cast<uint32_t*>(s + m->lay.live_cnt), nullptr,
-                            nullptr, stream));
+                            g.run_stride, runs, nruns, reinterpret_cast<uint32_t*>(m->d_lists + m->ll.live_cnt),
+                            stream));
   LA_HIP(hipMemcpyAsync(host_runs, runs, sizeof(uint32_t) * (size_t)g.rows * g.run_stride, hipMemcpyDeviceToHost,
                         stream));
   LA_HIP(hipMemcpyAsync(host_nruns, nruns, sizeof(uint32_t) * (size_t)g.rows, hipMemcpyDeviceToHost, stream));
@@ -348,6 +368,7 @@ void lite_attn_free_mask(lite_attn_mask_t* m) {
   }
   if (m->d_bits) (void)hipFree(m->d_bits);
   if (m->d_stats) (void)hipFree(m->d_stats);
+  if (m->d_lists) (void)hipFree(m->d_lists);
   if (m->own.base) (void)hipFree(m->own.base);
   if (m->events) {
     for (size_t x = 0; x < 3 * (size_t)m->desc.max_steps; ++x) (void)hipEventDestroy(m->events[x]);

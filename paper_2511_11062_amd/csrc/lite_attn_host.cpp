@@ -48,24 +48,29 @@ Geometry geometry(const lite_attn_desc_t& d) {
   return g;
 }
 
-ScratchLayout scratch_layout(const Geometry& g) {
-  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-  ScratchLayout l;
+namespace {
+size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+}  // namespace
+
+ListLayout list_layout(const Geometry& g) {
+  ListLayout l;
   size_t at = 0;
   l.stats = at;
-  at += up(3 * sizeof(unsigned long long));
+  at += up256(3 * sizeof(unsigned long long));
+  l.done = at;
+  at += up256(sizeof(uint32_t) * (size_t)g.BH);
   l.nruns = at;
-  at += up(sizeof(uint32_t) * (size_t)g.rows);
+  at += up256(sizeof(uint32_t) * (size_t)g.rows);
   l.live_cnt = at;
-  at += up(sizeof(uint32_t) * (size_t)g.rows);
+  at += up256(sizeof(uint32_t) * (size_t)g.rows);
   l.order = at;
-  at += up(sizeof(uint32_t) * (size_t)g.rows);
+  at += up256(sizeof(uint32_t) * (size_t)g.rows);
   l.runs = at;
-  at += up(sizeof(uint32_t) * (size_t)g.rows * g.run_stride);
-  l.vt = at;
-  at += up(sizeof(uint16_t) * (size_t)g.BH * 128 * ((size_t)g.Tk * 128));
+  at += up256(sizeof(uint32_t) * (size_t)g.rows * g.run_stride);
   l.total = at;
   return l;
 }
+
+size_t vt_bytes(const Geometry& g) { return up256(sizeof(uint16_t) * (size_t)g.BH * 128 * ((size_t)g.Tk * 128)); }
 
 }  // namespace la

@@ -15,17 +15,23 @@ struct FwdParams {
   uint16_t* out;
   int64_t stride_b, stride_h, stride_n;  // elements
   int H, N, Tq, Tk, W;                   // W = uint64 words per mask row
-  const uint32_t* runs;                  // [rows][run_stride] Skip-List: start | end << 16 per run of live tiles
+  uint32_t* runs;                        // [rows][run_stride] Skip-List: start | end << 16 per run of live tiles
   int run_stride;
-  const uint32_t* nruns;                 // [rows] runs per row
-  const uint32_t* live_cnt;              // [rows] live tiles per row
+  uint32_t* nruns;                       // [rows] runs per row
+  uint32_t* live_cnt;                    // [rows] live tiles per row
   uint64_t* bits;                        // [rows][W]
-  unsigned long long* stat_newly;        // counter of the current step
+  unsigned long long* stat_skipped_in;   // counters of the current step
+  unsigned long long* stat_newly;
+  unsigned long long* stat_runs;
   float thr;                             // signed threshold, natural-log units of S
   float scale;                           // 1/sqrt(d)
   int protect_start, protect_len;
   int rows_total;                        // B*H*Tq
-  const uint32_t* order;                 // [B*H][Tq]: Q tiles of each head ranked by Skip-List length, longest first
+  uint32_t* order;                       // [B*H][Tq]: Q tiles of each head ranked by Skip-List length, longest first
+  // build_next != 0: the epilogue rewrites runs / nruns / live_cnt / order for the NEXT call from the mask this call
+  // leaves (done: [B*H] counters of finished rows per head, zero between launches); diagonal_first: visiting order
+  int build_next, diagonal_first;
+  uint32_t* done;
 };
 
 // Tile geometry of a layer, derived from its descriptor.
@@ -37,14 +43,15 @@ struct Geometry {
   int64_t rows;    // BH * Tq
 };
 
-// Byte offsets, inside one scratch buffer, of everything a call rebuilds from scratch (256-byte aligned pieces).
-struct ScratchLayout {
+// Byte offsets of the Skip-List buffers inside one allocation (256-byte aligned pieces).  Handles keep them between
+// calls (a call's epilogue leaves the next call's lists there); the handle-free entry point rebuilds them per call.
+struct ListLayout {
   size_t stats;     // 3 uint64 counters for callers without a handle (handles keep per-step counters of their own)
+  size_t done;      // [BH] uint32 finished rows per head (zero between launches)
   size_t nruns;     // [rows] uint32 runs per row
   size_t live_cnt;  // [rows] uint32 live tiles per row
   size_t order;     // [BH][Tq] uint32 row ranking
   size_t runs;      // [rows][run_stride] uint32 Skip-List
-  size_t vt;        // [BH][128][128*Tk] bf16 V^T
   size_t total;
 };
 
@@ -52,22 +59,25 @@ struct ScratchLayout {
 int check_desc(const lite_attn_desc_t* d);  // LITE_ATTN_OK or the error the header documents
 int check_call(const void* q, const void* k, const void* v, const void* out, float threshold);
 Geometry geometry(const lite_attn_desc_t& d);
-ScratchLayout scratch_layout(const Geometry& g);
+ListLayout list_layout(const Geometry& g);
+size_t vt_bytes(const Geometry& g);  // V^T scratch of one call: [BH][128][128*Tk] bf16, rounded up to 256 bytes
 
-// lite_attn.cpp: the launches of one attention call (Skip-List compaction, row schedule, V^T pre-pass, fused
-// attention) on `stream`, all scratch carved out of `scratch` by `lay`; `mid` (may be null) is recorded between the
-// pre-passes and the attention kernel.  Allocates nothing.
-hipError_t launch_call(const lite_attn_desc_t& d, const Geometry& g, const ScratchLayout& lay, char* scratch,
+// lite_attn.cpp: the launches of one attention call on `stream`.  lists_ready: the Skip-Lists and the row ranking in
+// `lists` already describe the mask (left by the previous call's epilogue); otherwise they are built first (Skip-List
+// compaction + row schedule kernels).  Then the V^T pre-pass into `vt` and the fused attention kernel, whose epilogue
+// builds the next call's lists if build_next.  `mid` (may be null) is recorded just before the attention kernel.
+// Allocates nothing.
+hipError_t launch_call(const lite_attn_desc_t& d, const Geometry& g, const ListLayout& ll, char* lists, uint16_t* vt,
                        const void* q, const void* k, const void* v, void* out, uint64_t* bits,
-                       unsigned long long* stats3, float threshold, hipStream_t stream, hipEvent_t mid);
+                       unsigned long long* stats3, float threshold, bool lists_ready, bool build_next,
+                       hipStream_t stream, hipEvent_t mid);
 int hip_fail(hipError_t e);  // remembers e for lite_attn_last_hip_error() and maps it to a lite_attn_error
 
 int fwd_lds_bytes();
 hipError_t prepare_fwd();
 hipError_t launch_clear(uint64_t* bits, size_t words, unsigned long long* stats, size_t nstats, hipStream_t st);
 hipError_t launch_compact(const uint64_t* bits, int rows, int Tq, int Tk, int W, int diagonal_first, int run_stride,
-                          uint32_t* runs, uint32_t* nruns, uint32_t* live_cnt, unsigned long long* stat_skipped_in,
-                          unsigned long long* stat_runs, hipStream_t st);
+                          uint32_t* runs, uint32_t* nruns, uint32_t* live_cnt, hipStream_t st);
 hipError_t launch_transpose_v(const uint16_t* v, uint16_t* vt, int64_t stride_b, int64_t stride_h, int64_t stride_n,
                               int BH, int H, int N, int Tk, hipStream_t st);
 hipError_t launch_order_rows(const uint32_t* live_cnt, int BH, int Tq, int Tk, uint32_t* order, hipStream_t st);

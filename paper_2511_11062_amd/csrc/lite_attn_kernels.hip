@@ -4,6 +4,8 @@
 //   compact_skiplist     : Skip-Mask row -> run-length list of its live K/V tiles, (start,end) per run
 //                          (Implementation, "Producer and Skip-List Optimization")
 //   order_rows_kernel    : per head, Q-tile rows ranked by Skip-List length (the launch order of the fused kernel)
+//                          (both only at the start of a trajectory or after a mask import: the fused kernel's
+//                          epilogue builds the next call's Skip-Lists and row ranking itself)
 //   transpose_v_kernel   : V -> V^T scratch, so that the PV operand is read from LDS like the QK operand
 //   lite_attn_fwd_kernel : fused tiled forward over the live tiles with the skip predicate
 //                          (Algorithm 2; eq. sparge_cond; tile recurrences of the Preliminaries)
@@ -71,69 +73,83 @@ __global__ void clear_state_kernel(uint64_t* bits, size_t words, unsigned long l
   for (size_t x = i; x < nstats; x += stride) stats[x] = 0;
 }
 
-// Skip-List compaction, one wave per Q-tile row (a wave takes kRowsPerWave consecutive rows).  The list is run-length
-// encoded as the paper describes: one entry (start | end << 16) per maximal run of consecutive live K/V tiles
-// [start, end), in visiting order (ascending, or -- "diagonal first" -- the tiles from the diagonal one to the last,
-// then those before the diagonal; a row then has at most floor(Tk/2) + 1 runs).  Lane l looks at bit l of each
-// 64-tile word: a live tile whose predecessor is not live starts a run, one whose successor is not live ends it;
-// the k-th start and the k-th end of a row belong to the same run, so the two 16-bit halves are written
-// independently at the position given by a ballot + prefix popcount.
+// A word that another workgroup (or an atomic of this one) may have written during this launch: read it from the
+// device-coherent level, past this CU's vector cache.
+__device__ __forceinline__ uint64_t load_fresh(const uint64_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t load_fresh(const uint32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Skip-List of ONE Q-tile row, built by one wave (all 64 lanes call this).  The list is run-length encoded as the
+// paper describes: one entry (start | end << 16) per maximal run of consecutive live K/V tiles [start, end), in
+// visiting order (ascending, or -- "diagonal first" -- the tiles from the diagonal one to the last, then those before
+// the diagonal; a row then has at most floor(Tk/2) + 1 runs).  Lane l looks at bit l of each 64-tile word: a live
+// tile whose predecessor is not live starts a run, one whose successor is not live ends it; the k-th start and the
+// k-th end of a row belong to the same run, so the two 16-bit halves are written independently at the position
+// given by a ballot + prefix popcount.  kFresh: the mask row may have been updated during this launch.
+// Returns the number of runs in ns and of live tiles in n (same in every lane).
+template <bool kFresh>
+__device__ __forceinline__ void compact_row(const uint64_t* __restrict__ mrow, int i, int Tk, int W,
+                                            int diagonal_first, uint32_t* __restrict__ row_runs, uint32_t& ns,
+                                            uint32_t& n) {
+  const int lane = threadIdx.x & 63;
+  uint16_t* out = reinterpret_cast<uint16_t*>(row_runs);
+  uint32_t ne = 0;
+  ns = 0;
+  n = 0;
+  // runs of the live tiles inside [lo, hi), ascending, appended to the list
+  auto emit = [&](int lo, int hi) {
+    auto live_word = [&](int w) -> uint64_t {  // bit l set = tile 64w+l lies in [lo, hi) and is not skipped
+      if (w < 0 || w >= W || 64 * w >= hi || 64 * w + 64 <= lo) return 0ull;
+      uint64_t m = ~(kFresh ? load_fresh(mrow + w) : mrow[w]);
+      if (hi - 64 * w < 64) m &= (1ull << (hi - 64 * w)) - 1ull;
+      if (lo > 64 * w) m &= ~((1ull << (lo - 64 * w)) - 1ull);
+      return m;
+    };
+    if (hi <= lo) return;
+    uint64_t prev = 0ull, cur = live_word(lo >> 6);
+    for (int w = lo >> 6; 64 * w < hi; ++w) {
+      const uint64_t next = live_word(w + 1);
+      const uint64_t starts = cur & ~((cur << 1) | (prev >> 63));
+      const uint64_t ends = cur & ~((cur >> 1) | (next << 63));
+      const uint64_t below = (1ull << lane) - 1ull;
+      const int j = 64 * w + lane;
+      if ((starts >> lane) & 1ull) out[2 * (ns + __popcll(starts & below))] = (uint16_t)j;
+      if ((ends >> lane) & 1ull) out[2 * (ne + __popcll(ends & below)) + 1] = (uint16_t)(j + 1);
+      ns += __popcll(starts);
+      ne += __popcll(ends);
+      n += __popcll(cur);
+      prev = cur;
+      cur = next;
+    }
+  };
+  if (diagonal_first) {  // visiting order i, i+1, ..., Tk-1, 0, ..., i-1: the diagonal tile comes first
+    const int d = min(i, Tk);
+    emit(d, Tk);
+    emit(0, d);
+  } else {
+    emit(0, Tk);
+  }
+}
+
+// Skip-List compaction as a kernel of its own (the first call of a trajectory, and after the mask was imported;
+// otherwise the fused kernel's epilogue has already built the lists of the next call): a wave takes kRowsPerWave
+// consecutive rows (Implementation, "Producer and Skip-List Optimization").
 __global__ __launch_bounds__(256) void compact_skiplist(const uint64_t* __restrict__ bits, int rows, int Tq, int Tk,
                                                          int W, int diagonal_first, int run_stride,
                                                          uint32_t* __restrict__ runs, uint32_t* __restrict__ nruns,
-                                                         uint32_t* __restrict__ live_cnt,
-                                                         unsigned long long* __restrict__ stat_skipped_in,
-                                                         unsigned long long* __restrict__ stat_runs) {
+                                                         uint32_t* __restrict__ live_cnt) {
   const int lane = threadIdx.x & 63;
   const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
-  unsigned long long skipped_sum = 0, runs_sum = 0;  // one pair of atomics per wave, not per row
   for (int row = wave * kRowsPerWave; row < min(rows, (wave + 1) * kRowsPerWave); ++row) {
-    const uint64_t* mrow = bits + (size_t)row * W;
-    uint16_t* out = reinterpret_cast<uint16_t*>(runs + (size_t)row * run_stride);
-    uint32_t ns = 0, ne = 0, n = 0;
-    // runs of the live tiles inside [lo, hi), ascending, appended to the list
-    auto emit = [&](int lo, int hi) {
-      auto live_word = [&](int w) -> uint64_t {  // bit l set = tile 64w+l lies in [lo, hi) and is not skipped
-        if (w < 0 || w >= W || 64 * w >= hi || 64 * w + 64 <= lo) return 0ull;
-        uint64_t m = ~mrow[w];
-        if (hi - 64 * w < 64) m &= (1ull << (hi - 64 * w)) - 1ull;
-        if (lo > 64 * w) m &= ~((1ull << (lo - 64 * w)) - 1ull);
-        return m;
-      };
-      if (hi <= lo) return;
-      uint64_t prev = 0ull, cur = live_word(lo >> 6);
-      for (int w = lo >> 6; 64 * w < hi; ++w) {
-        const uint64_t next = live_word(w + 1);
-        const uint64_t starts = cur & ~((cur << 1) | (prev >> 63));
-        const uint64_t ends = cur & ~((cur >> 1) | (next << 63));
-        const uint64_t below = (1ull << lane) - 1ull;
-        const int j = 64 * w + lane;
-        if ((starts >> lane) & 1ull) out[2 * (ns + __popcll(starts & below))] = (uint16_t)j;
-        if ((ends >> lane) & 1ull) out[2 * (ne + __popcll(ends & below)) + 1] = (uint16_t)(j + 1);
-        ns += __popcll(starts);
-        ne += __popcll(ends);
-        n += __popcll(cur);
-        prev = cur;
-        cur = next;
-      }
-    };
-    if (diagonal_first) {  // visiting order i, i+1, ..., Tk-1, 0, ..., i-1: the diagonal tile comes first
-      const int i = min(row % Tq, Tk);
-      emit(i, Tk);
-      emit(0, i);
-    } else {
-      emit(0, Tk);
-    }
+    uint32_t ns, n;
+    compact_row<false>(bits + (size_t)row * W, row % Tq, Tk, W, diagonal_first, runs + (size_t)row * run_stride, ns, n);
     if (lane == 0) {
       nruns[row] = ns;
       live_cnt[row] = n;
     }
-    skipped_sum += (unsigned long long)(Tk - n);
-    runs_sum += ns;
-  }
-  if (lane == 0) {
-    if (stat_skipped_in && skipped_sum) atomicAdd(stat_skipped_in, skipped_sum);
-    if (stat_runs && runs_sum) atomicAdd(stat_runs, runs_sum);
   }
 }
 
@@ -157,17 +173,17 @@ __device__ __forceinline__ float other_half_sum(float x) {
 }
 
 // Row schedule.  For every head, ranks its Q-tile rows by the length of their Skip-List, longest first (counting
-// sort: one workgroup per head, histogram in LDS).  The fused kernel walks each head's rows in this order, so that
-// the rows left over at the end of the launch are the shortest ones, and spreads rank-chunks of every head over
-// all XCDs, so that every XCD gets the same mix of long and short rows whatever the sparsity of individual heads.
-__global__ __launch_bounds__(256) void order_rows_kernel(const uint32_t* __restrict__ live_cnt, int Tq, int Tk,
-                                                          uint32_t* __restrict__ order) {
-  extern __shared__ uint32_t hist[];  // Tk + 1 bins; bin b counts rows with Tk - b live tiles
-  const int bh = blockIdx.x, tid = threadIdx.x;
-  const uint32_t* cnt = live_cnt + (size_t)bh * Tq;
-  for (int b = tid; b <= Tk; b += 256) hist[b] = 0;
+// sort by one workgroup, histogram of Tk + 1 bins in LDS).  The fused kernel walks each head's rows in this order, so
+// that the rows left over at the end of the launch are the shortest ones, and spreads rank-chunks of every head over
+// all XCDs, so that every XCD gets the same share of long and short rows whatever the sparsity of individual heads.
+// kFresh: the counts were written by other workgroups of this launch.
+template <bool kFresh>
+__device__ __forceinline__ void rank_head_rows(const uint32_t* __restrict__ cnt, int Tq, int Tk,
+                                               uint32_t* __restrict__ order_head, uint32_t* hist, int tid, int nthr) {
+  for (int b = tid; b <= Tk; b += nthr) hist[b] = 0;
   __syncthreads();
-  for (int i = tid; i < Tq; i += 256) atomicAdd(&hist[Tk - min((int)cnt[i], Tk)], 1u);
+  for (int i = tid; i < Tq; i += nthr)
+    atomicAdd(&hist[Tk - min((int)(kFresh ? load_fresh(cnt + i) : cnt[i]), Tk)], 1u);
   __syncthreads();
   if (tid == 0) {  // exclusive prefix sum over at most 16384 bins
     uint32_t run = 0;
@@ -178,10 +194,17 @@ __global__ __launch_bounds__(256) void order_rows_kernel(const uint32_t* __restr
     }
   }
   __syncthreads();
-  for (int i = tid; i < Tq; i += 256) {
-    const uint32_t pos = atomicAdd(&hist[Tk - min((int)cnt[i], Tk)], 1u);
-    order[(size_t)bh * Tq + pos] = (uint32_t)i;
+  for (int i = tid; i < Tq; i += nthr) {
+    const uint32_t pos = atomicAdd(&hist[Tk - min((int)(kFresh ? load_fresh(cnt + i) : cnt[i]), Tk)], 1u);
+    order_head[pos] = (uint32_t)i;
   }
+}
+
+__global__ __launch_bounds__(256) void order_rows_kernel(const uint32_t* __restrict__ live_cnt, int Tq, int Tk,
+                                                          uint32_t* __restrict__ order) {
+  extern __shared__ uint32_t hist[];  // Tk + 1 bins; bin b counts rows with Tk - b live tiles
+  rank_head_rows<false>(live_cnt + (size_t)blockIdx.x * Tq, Tq, Tk, order + (size_t)blockIdx.x * Tq, hist, threadIdx.x,
+                        256);
 }
 
 // V -> V^T pre-pass.  The PV product contracts over the K/V index, so the matrix cores want, per lane, 8 V values
@@ -609,6 +632,10 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
   const_u32_ptr runs = (const_u32_ptr)(p.runs + (size_t)row * p.run_stride);
   const int nruns = (int)p.nruns[row];
   int* flags = reinterpret_cast<int*>(smem + kFlagsOff);
+  if (tid == 0) {  // statistics of the step: tiles skipped on entry, Skip-List entries read
+    atomicAdd(p.stat_skipped_in, (unsigned long long)(p.Tk - cnt));
+    atomicAdd(p.stat_runs, (unsigned long long)nruns);
+  }
 
   Lane<QB> ln;
   ln.hi = lane >> 5;
@@ -810,6 +837,39 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
       *reinterpret_cast<uint4*>(ob + (int64_t)grow * p.stride_n + 8 * (tid & 15)) =
           *reinterpret_cast<const uint4*>(sO + r * kORow + 16 * (tid & 15));
   }
+
+  // ---- second epilogue: the Skip-List this row will walk in the NEXT call, compacted from the mask row as this call
+  // leaves it (the row's list is private to this workgroup: it is overwritten in place, after its last read).  The
+  // workgroup that finishes a head's last row also ranks the head's rows for the next call. ----
+  // (The kernel arguments used here are read again from the argument segment instead of being kept in scalar
+  // registers across the main loop, which has none to spare.)
+  typedef const __attribute__((address_space(4))) FwdParams* const_params_ptr;
+  const_params_ptr e = (const_params_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(e));
+  if (e->build_next) {
+    __threadfence();  // this workgroup's own mask updates (atomics of thread 0) are performed before they are read back
+    const int Tq = e->Tq, Tk = e->Tk;
+    uint32_t* const live_cnt = e->live_cnt;
+    uint32_t* const done = e->done;
+    if (wave == 0) {
+      uint32_t ns, n;
+      compact_row<true>(e->bits + (size_t)row * e->W, i, Tk, e->W, e->diagonal_first,
+                        e->runs + (size_t)row * e->run_stride, ns, n);
+      if (lane == 0) {
+        e->nruns[row] = ns;
+        live_cnt[row] = n;
+        __threadfence();  // the count is visible before this row is reported done
+        flags[0] = atomicAdd(done + bh, 1u) == (uint32_t)Tq - 1u ? 1 : 0;
+      }
+    }
+    __syncthreads();  // also: every thread is done with the staging of O, which the histogram below overwrites
+    if (flags[0]) {
+      __threadfence();
+      rank_head_rows<true>(live_cnt + (size_t)bh * Tq, Tq, Tk, e->order + (size_t)bh * Tq,
+                           reinterpret_cast<uint32_t*>(smem), tid, kThreads);
+      if (tid == 0) done[bh] = 0;  // ready for the next launch
+    }
+  }
 }
 
 int fwd_lds_bytes() { return kLdsBytes; }
@@ -824,11 +884,9 @@ hipError_t launch_clear(uint64_t* bits, size_t words, unsigned long long* stats,
 }
 
 hipError_t launch_compact(const uint64_t* bits, int rows, int Tq, int Tk, int W, int diagonal_first, int run_stride,
-                          uint32_t* runs, uint32_t* nruns, uint32_t* live_cnt, unsigned long long* stat_skipped_in,
-                          unsigned long long* stat_runs, hipStream_t st) {
+                          uint32_t* runs, uint32_t* nruns, uint32_t* live_cnt, hipStream_t st) {
   hipLaunchKernelGGL(compact_skiplist, dim3((rows + 4 * kRowsPerWave - 1) / (4 * kRowsPerWave)), dim3(256), 0, st, bits,
-                     rows, Tq, Tk, W, diagonal_first,
-                     run_stride, runs, nruns, live_cnt, stat_skipped_in, stat_runs);
+                     rows, Tq, Tk, W, diagonal_first, run_stride, runs, nruns, live_cnt);
   return hipGetLastError();
 }
 

@@ -48,17 +48,18 @@ extern "C" int lite_attn_fwd_static(const void* q, const void* k, const void* v,
   if (rc != LITE_ATTN_OK) return rc;
   if (!dev_skip_mask || ((uintptr_t)dev_skip_mask & 7)) return LITE_ATTN_EINVAL;
   const la::Geometry geo = la::geometry(*desc);
-  const la::ScratchLayout lay = la::scratch_layout(geo);
-  if (lay.total > (size_t)LITE_ATTN_STATIC_SCRATCH_BYTES) return LITE_ATTN_ESCRATCH;
+  const la::ListLayout ll = la::list_layout(geo);  // the lists first, V^T behind them
+  if (ll.total + la::vt_bytes(geo) > (size_t)LITE_ATTN_STATIC_SCRATCH_BYTES) return LITE_ATTN_ESCRATCH;
   char* ptr = nullptr;
   rc = scratch_of_current_device(&ptr);
   if (rc != LITE_ATTN_OK) return rc;
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   // the array keeps the previous call's contents: the counters the kernels add to start at zero (fill kernel, not a
   // memset node); Skip-List, row schedule and V^T are written in full, for this call's shape, before they are read
-  unsigned long long* stats = reinterpret_cast<unsigned long long*>(ptr + lay.stats);
+  unsigned long long* stats = reinterpret_cast<unsigned long long*>(ptr + ll.stats);
   hipError_t e = la::launch_clear(nullptr, 0, stats, 3, stream);
-  if (e == hipSuccess)
-    e = la::launch_call(*desc, geo, lay, ptr, q, k, v, out, dev_skip_mask, stats, threshold, stream, nullptr);
+  if (e == hipSuccess)  // lists rebuilt from the caller's mask on every call, none left behind for a next one
+    e = la::launch_call(*desc, geo, ll, ptr, reinterpret_cast<uint16_t*>(ptr + ll.total), q, k, v, out, dev_skip_mask,
+                        stats, threshold, /*lists_ready=*/false, /*build_next=*/false, stream, nullptr);
   return e == hipSuccess ? LITE_ATTN_OK : la::hip_fail(e);
 }

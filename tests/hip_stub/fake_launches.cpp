@@ -11,24 +11,21 @@ int fwd_lds_bytes() { return 0; }
 hipError_t prepare_fwd() { return hipSuccess; }
 
 hipError_t launch_clear(uint64_t* bits, size_t words, unsigned long long* stats, size_t nstats, hipStream_t) {
-  memset(bits, 0, words * sizeof(uint64_t));
-  memset(stats, 0, nstats * sizeof(unsigned long long));
+  if (words) memset(bits, 0, words * sizeof(uint64_t));
+  if (nstats) memset(stats, 0, nstats * sizeof(unsigned long long));
   return hipSuccess;
 }
 
 hipError_t launch_compact(const uint64_t* bits, int rows, int, int Tk, int W, int, int run_stride, uint32_t* runs,
-                          uint32_t* nruns, uint32_t* live_cnt, unsigned long long* stat_skipped_in,
-                          unsigned long long* stat_runs, hipStream_t) {
+                          uint32_t* nruns, uint32_t* live_cnt, hipStream_t) {
   uint64_t any = 0;
   for (size_t x = 0; x < (size_t)rows * W; ++x) any |= bits[x];  // reads the whole mask
   for (int r = 0; r < rows; ++r) {                               // one run covering the row: [0, Tk)
     memset(runs + (size_t)r * run_stride, 0, sizeof(uint32_t) * run_stride);
     runs[(size_t)r * run_stride] = (uint32_t)Tk << 16;
     nruns[r] = 1;
-    live_cnt[r] = (uint32_t)Tk;
+    live_cnt[r] = (uint32_t)Tk + (any ? 0u : 0u);
   }
-  if (stat_skipped_in) *stat_skipped_in += any ? 1 : 0;
-  if (stat_runs) *stat_runs += (unsigned long long)rows;
   return hipSuccess;
 }
 
@@ -51,7 +48,19 @@ hipError_t launch_fwd(const FwdParams& p, bool, hipStream_t) {
   (void)sink;
   p.bits[0] |= 0;
   p.bits[rows * p.W - 1] |= 0;
+  *p.stat_skipped_in += 0;
   *p.stat_newly += 0;
+  *p.stat_runs += (unsigned long long)rows;
+  if (p.build_next) {  // the epilogue rewrites the lists in full and leaves the per-head counters at zero
+    memset(p.runs, 0, sizeof(uint32_t) * rows * p.run_stride);
+    for (size_t r = 0; r < rows; ++r) {
+      p.runs[r * p.run_stride] = (uint32_t)p.Tk << 16;
+      p.nruns[r] = 1;
+      p.live_cnt[r] = (uint32_t)p.Tk;
+      p.order[r] = (uint32_t)(r % p.Tq);
+    }
+    for (size_t h = 0; h < rows / p.Tq; ++h) p.done[h] = 0;
+  }
   return hipSuccess;
 }
 

@@ -234,6 +234,43 @@ def test_threshold_schedule_checked_against_the_oracle():
     assert not parted.any()         # (deterministic inputs: no tile of this sequence sits inside the band)
 
 
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+def test_lists_built_in_the_epilogue_equal_recompacted_lists(flags):
+    """From the second call of a trajectory on, the Skip-Lists and the row ranking a call walks were left by the
+    previous call's epilogue.  Run a sequence twice: once as it is, once with the mask exported and imported again
+    between the calls, which makes every call rebuild its lists with the compaction and ranking kernels.  Outputs,
+    masks and the per-step statistics (tiles skipped on entry, Skip-List entries read) must be identical.  Every output
+    buffer starts as NaN, so a row that the ranking lost would show."""
+    from paper_2511_11062_amd import lite_attn as la
+    wl = small("epi", 5, (3, 31, 41), 5, text=100, seed=61)               # 5 heads, N = 3913: 31 tiles, ragged
+    seq = inputs.DriftSequence(wl, "cpu")
+    data = [tuple(x.cuda().contiguous() for x in next(seq)) for _ in range(5)]
+    thr = [-3.5, -3.0, -2.5, -1.5, -1.0]
+
+    def run(reimport):
+        h = la.lite_attn_init_mask(1, wl.heads, wl.seqlen, protect=wl.protect, max_steps=5, flags=flags)
+        res = []
+        try:
+            for t, (q, k, v) in enumerate(data):
+                if reimport and t > 0:
+                    la.lite_attn_mask_import(h, la.lite_attn_mask_export(h), t)
+                o = torch.full_like(q, float("nan"))
+                la.lite_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), h, thr[t], t)
+                torch.cuda.synchronize()
+                st = la.lite_attn_skip_stats(h, t)
+                res.append((o, la.lite_attn_mask_export(h).copy(),
+                            (st.tiles_skipped_in, st.tiles_newly_marked, st.live_list_bytes)))
+        finally:
+            la.lite_attn_free_mask(h)
+        return res
+
+    a, b = run(False), run(True)
+    for t in range(5):
+        assert torch.isfinite(a[t][0]).all() and torch.equal(a[t][0], b[t][0]), "step %d" % t
+        assert np.array_equal(a[t][1], b[t][1]) and a[t][2] == b[t][2], "step %d: %s vs %s" % (t, a[t][2], b[t][2])
+    assert a[4][2][0] > a[1][2][0] > 0                                    # the mask grew along the sequence
+
+
 def test_shared_scratch_context():
     """Two layers of different shapes attached to one context share one scratch buffer and the context's stream:
     interleaved calls on that stream give, bit for bit, what handles with scratch of their own give; a sharing
