@@ -29,7 +29,7 @@ struct lite_attn_mask {
   la::Geometry geo;
   la::ListLayout ll;
   uint64_t* d_bits;
-  char* d_lists;      // Skip-Lists, row ranking, per-head counters (layout ll); kept between calls
+  char* d_lists;      // Skip-Lists and row ranking (layout ll); kept between calls
   bool lists_valid;   // the lists describe the mask as it stands (left by the previous call's epilogue)
   unsigned long long* d_stats;  // [max_steps][3]: skipped on entry, newly marked, Skip-List runs
   la_scratch own;               // used when ctx == nullptr
@@ -65,9 +65,10 @@ hipError_t launch_call(const lite_attn_desc_t& d, const Geometry& g, const ListL
   if (!lists_ready) {
     e = launch_compact(bits, (int)g.rows, g.Tq, g.Tk, g.W, diagonal_first, g.run_stride, runs, nruns, live_cnt, stream);
     if (e != hipSuccess) return e;
-    e = launch_order_rows(live_cnt, g.BH, g.Tq, g.Tk, order, stream);
-    if (e != hipSuccess) return e;
   }
+  // ranking a head's rows needs the counts of all of them: a kernel of its own (one workgroup per head)
+  e = launch_order_rows(live_cnt, g.BH, g.Tq, g.Tk, order, stream);
+  if (e != hipSuccess) return e;
   e = launch_transpose_v(static_cast<const uint16_t*>(v), vt, d.stride_b, d.stride_h, d.stride_n, g.BH, d.heads,
                          d.seqlen, g.Tk, stream);
   if (e != hipSuccess) return e;
@@ -88,7 +89,6 @@ hipError_t launch_call(const lite_attn_desc_t& d, const Geometry& g, const ListL
   p.order = order;
   p.build_next = build_next ? 1 : 0;
   p.diagonal_first = diagonal_first;
-  p.done = reinterpret_cast<uint32_t*>(lists + ll.done);
   if (mid) {
     e = hipEventRecord(mid, stream);
     if (e != hipSuccess) return e;
@@ -157,8 +157,6 @@ int init_common(const lite_attn_desc_t* desc, lite_attn_ctx* ctx, lite_attn_mask
     if (e == hipSuccess) e = hipMalloc(&m->d_lists, m->ll.total);
     if (e == hipSuccess) e = la::prepare_fwd();
     if (e == hipSuccess) e = la::launch_clear(m->d_bits, words, m->d_stats, nstats, st);
-    if (e == hipSuccess)  // the per-head counters of finished rows (and the unused counter slot in front of them)
-      e = la::launch_clear(reinterpret_cast<uint64_t*>(m->d_lists), m->ll.nruns / sizeof(uint64_t), nullptr, 0, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) rc = hip_fail(e);
   }

@@ -57,8 +57,6 @@ ListLayout list_layout(const Geometry& g) {
   size_t at = 0;
   l.stats = at;
   at += up256(3 * sizeof(unsigned long long));
-  l.done = at;
-  at += up256(sizeof(uint32_t) * (size_t)g.BH);
   l.nruns = at;
   at += up256(sizeof(uint32_t) * (size_t)g.rows);
   l.live_cnt = at;

@@ -28,10 +28,9 @@ struct FwdParams {
   int protect_start, protect_len;
   int rows_total;                        // B*H*Tq
   uint32_t* order;                       // [B*H][Tq]: Q tiles of each head ranked by Skip-List length, longest first
-  // build_next != 0: the epilogue rewrites runs / nruns / live_cnt / order for the NEXT call from the mask this call
-  // leaves (done: [B*H] counters of finished rows per head, zero between launches); diagonal_first: visiting order
+  // build_next != 0: the epilogue rewrites runs / nruns / live_cnt for the NEXT call from the mask this call leaves;
+  // diagonal_first: visiting order of the lists
   int build_next, diagonal_first;
-  uint32_t* done;
 };
 
 // Tile geometry of a layer, derived from its descriptor.
@@ -47,7 +46,6 @@ struct Geometry {
 // calls (a call's epilogue leaves the next call's lists there); the handle-free entry point rebuilds them per call.
 struct ListLayout {
   size_t stats;     // 3 uint64 counters for callers without a handle (handles keep per-step counters of their own)
-  size_t done;      // [BH] uint32 finished rows per head (zero between launches)
   size_t nruns;     // [rows] uint32 runs per row
   size_t live_cnt;  // [rows] uint32 live tiles per row
   size_t order;     // [BH][Tq] uint32 row ranking
@@ -62,10 +60,10 @@ Geometry geometry(const lite_attn_desc_t& d);
 ListLayout list_layout(const Geometry& g);
 size_t vt_bytes(const Geometry& g);  // V^T scratch of one call: [BH][128][128*Tk] bf16, rounded up to 256 bytes
 
-// lite_attn.cpp: the launches of one attention call on `stream`.  lists_ready: the Skip-Lists and the row ranking in
-// `lists` already describe the mask (left by the previous call's epilogue); otherwise they are built first (Skip-List
-// compaction + row schedule kernels).  Then the V^T pre-pass into `vt` and the fused attention kernel, whose epilogue
-// builds the next call's lists if build_next.  `mid` (may be null) is recorded just before the attention kernel.
+// lite_attn.cpp: the launches of one attention call on `stream`.  lists_ready: the Skip-Lists in `lists` already
+// describe the mask (left by the previous call's epilogue); otherwise the compaction kernel builds them first.  Then
+// the row schedule, the V^T pre-pass into `vt` and the fused attention kernel, whose epilogue builds the next call's
+// lists if build_next.  `mid` (may be null) is recorded just before the attention kernel.
 // Allocates nothing.
 hipError_t launch_call(const lite_attn_desc_t& d, const Geometry& g, const ListLayout& ll, char* lists, uint16_t* vt,
                        const void* q, const void* k, const void* v, void* out, uint64_t* bits,

@@ -2,10 +2,9 @@
 //
 //   clear_state_kernel   : zero the Skip-Mask and the statistics (step 0)
 //   compact_skiplist     : Skip-Mask row -> run-length list of its live K/V tiles, (start,end) per run
-//                          (Implementation, "Producer and Skip-List Optimization")
+//                          (Implementation, "Producer and Skip-List Optimization"); only at the start of a trajectory
+//                          or after a mask import: the fused kernel's epilogue builds the next call's Skip-Lists
 //   order_rows_kernel    : per head, Q-tile rows ranked by Skip-List length (the launch order of the fused kernel)
-//                          (both only at the start of a trajectory or after a mask import: the fused kernel's
-//                          epilogue builds the next call's Skip-Lists and row ranking itself)
 //   transpose_v_kernel   : V -> V^T scratch, so that the PV operand is read from LDS like the QK operand
 //   lite_attn_fwd_kernel : fused tiled forward over the live tiles with the skip predicate
 //                          (Algorithm 2; eq. sparge_cond; tile recurrences of the Preliminaries)
@@ -61,7 +60,9 @@ constexpr int kStageBytes = kSub * 256;  // one K or V stage: 64 rows x 128 bf16
 constexpr int kKOff = 0;                 // K stage p at kKOff + p * kStageBytes
 constexpr int kVOff = 2 * kStageBytes;   // V stage p at kVOff + p * kStageBytes
 constexpr int kFlagsOff = 4 * kStageBytes;  // 8 ints [tile parity][wave] + 64 dummy ints
-constexpr int kLdsBytes = kFlagsOff + 8 * 4 + 64 * 4;
+constexpr int kFiredOff = kFlagsOff + 8 * 4 + 64 * 4;  // W uint64: mask bits this workgroup set during the call
+constexpr int kMaxMaskWords = 256;                     // ceil(16383 / 64)
+constexpr int kLdsBytes = kFiredOff + 8 * kMaxMaskWords;
 constexpr int kORow = 272;        // bytes per O row in the epilogue staging (reuses the stage buffers)
 
 constexpr int kRowsPerWave = 8;  // Q-tile rows compacted by one wave of compact_skiplist
@@ -73,25 +74,17 @@ __global__ void clear_state_kernel(uint64_t* bits, size_t words, unsigned long l
   for (size_t x = i; x < nstats; x += stride) stats[x] = 0;
 }
 
-// A word that another workgroup (or an atomic of this one) may have written during this launch: read it from the
-// device-coherent level, past this CU's vector cache.
-__device__ __forceinline__ uint64_t load_fresh(const uint64_t* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint32_t load_fresh(const uint32_t* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // Skip-List of ONE Q-tile row, built by one wave (all 64 lanes call this).  The list is run-length encoded as the
 // paper describes: one entry (start | end << 16) per maximal run of consecutive live K/V tiles [start, end), in
 // visiting order (ascending, or -- "diagonal first" -- the tiles from the diagonal one to the last, then those before
 // the diagonal; a row then has at most floor(Tk/2) + 1 runs).  Lane l looks at bit l of each 64-tile word: a live
 // tile whose predecessor is not live starts a run, one whose successor is not live ends it; the k-th start and the
 // k-th end of a row belong to the same run, so the two 16-bit halves are written independently at the position
-// given by a ballot + prefix popcount.  kFresh: the mask row may have been updated during this launch.
-// Returns the number of runs in ns and of live tiles in n (same in every lane).
-template <bool kFresh>
-__device__ __forceinline__ void compact_row(const uint64_t* __restrict__ mrow, int i, int Tk, int W,
+// given by a ballot + prefix popcount.  `extra` (may be null, W words, any address space the caller's lambda reads):
+// bits to be OR-ed into the mask row first.  Returns the number of runs in ns and of live tiles in n (same in every
+// lane).
+template <class ExtraBits>
+__device__ __forceinline__ void compact_row(const uint64_t* __restrict__ mrow, ExtraBits extra, int i, int Tk, int W,
                                             int diagonal_first, uint32_t* __restrict__ row_runs, uint32_t& ns,
                                             uint32_t& n) {
   const int lane = threadIdx.x & 63;
@@ -103,7 +96,7 @@ __device__ __forceinline__ void compact_row(const uint64_t* __restrict__ mrow, i
   auto emit = [&](int lo, int hi) {
     auto live_word = [&](int w) -> uint64_t {  // bit l set = tile 64w+l lies in [lo, hi) and is not skipped
       if (w < 0 || w >= W || 64 * w >= hi || 64 * w + 64 <= lo) return 0ull;
-      uint64_t m = ~(kFresh ? load_fresh(mrow + w) : mrow[w]);
+      uint64_t m = ~(mrow[w] | extra(w));
       if (hi - 64 * w < 64) m &= (1ull << (hi - 64 * w)) - 1ull;
       if (lo > 64 * w) m &= ~((1ull << (lo - 64 * w)) - 1ull);
       return m;
@@ -145,7 +138,8 @@ __global__ __launch_bounds__(256) void compact_skiplist(const uint64_t* __restri
   const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
   for (int row = wave * kRowsPerWave; row < min(rows, (wave + 1) * kRowsPerWave); ++row) {
     uint32_t ns, n;
-    compact_row<false>(bits + (size_t)row * W, row % Tq, Tk, W, diagonal_first, runs + (size_t)row * run_stride, ns, n);
+    compact_row(bits + (size_t)row * W, [](int) { return 0ull; }, row % Tq, Tk, W, diagonal_first,
+                runs + (size_t)row * run_stride, ns, n);
     if (lane == 0) {
       nruns[row] = ns;
       live_cnt[row] = n;
@@ -173,17 +167,17 @@ __device__ __forceinline__ float other_half_sum(float x) {
 }
 
 // Row schedule.  For every head, ranks its Q-tile rows by the length of their Skip-List, longest first (counting
-// sort by one workgroup, histogram of Tk + 1 bins in LDS).  The fused kernel walks each head's rows in this order, so
-// that the rows left over at the end of the launch are the shortest ones, and spreads rank-chunks of every head over
-// all XCDs, so that every XCD gets the same share of long and short rows whatever the sparsity of individual heads.
-// kFresh: the counts were written by other workgroups of this launch.
-template <bool kFresh>
-__device__ __forceinline__ void rank_head_rows(const uint32_t* __restrict__ cnt, int Tq, int Tk,
-                                               uint32_t* __restrict__ order_head, uint32_t* hist, int tid, int nthr) {
-  for (int b = tid; b <= Tk; b += nthr) hist[b] = 0;
+// sort: one workgroup per head, histogram in LDS).  The fused kernel walks each head's rows in this order, so that
+// the rows left over at the end of the launch are the shortest ones, and spreads rank-chunks of every head over
+// all XCDs, so that every XCD gets the same mix of long and short rows whatever the sparsity of individual heads.
+__global__ __launch_bounds__(256) void order_rows_kernel(const uint32_t* __restrict__ live_cnt, int Tq, int Tk,
+                                                          uint32_t* __restrict__ order) {
+  extern __shared__ uint32_t hist[];  // Tk + 1 bins; bin b counts rows with Tk - b live tiles
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  const uint32_t* cnt = live_cnt + (size_t)bh * Tq;
+  for (int b = tid; b <= Tk; b += 256) hist[b] = 0;
   __syncthreads();
-  for (int i = tid; i < Tq; i += nthr)
-    atomicAdd(&hist[Tk - min((int)(kFresh ? load_fresh(cnt + i) : cnt[i]), Tk)], 1u);
+  for (int i = tid; i < Tq; i += 256) atomicAdd(&hist[Tk - min((int)cnt[i], Tk)], 1u);
   __syncthreads();
   if (tid == 0) {  // exclusive prefix sum over at most 16384 bins
     uint32_t run = 0;
@@ -194,17 +188,10 @@ __device__ __forceinline__ void rank_head_rows(const uint32_t* __restrict__ cnt,
     }
   }
   __syncthreads();
-  for (int i = tid; i < Tq; i += nthr) {
-    const uint32_t pos = atomicAdd(&hist[Tk - min((int)(kFresh ? load_fresh(cnt + i) : cnt[i]), Tk)], 1u);
-    order_head[pos] = (uint32_t)i;
+  for (int i = tid; i < Tq; i += 256) {
+    const uint32_t pos = atomicAdd(&hist[Tk - min((int)cnt[i], Tk)], 1u);
+    order[(size_t)bh * Tq + pos] = (uint32_t)i;
   }
-}
-
-__global__ __launch_bounds__(256) void order_rows_kernel(const uint32_t* __restrict__ live_cnt, int Tq, int Tk,
-                                                          uint32_t* __restrict__ order) {
-  extern __shared__ uint32_t hist[];  // Tk + 1 bins; bin b counts rows with Tk - b live tiles
-  rank_head_rows<false>(live_cnt + (size_t)blockIdx.x * Tq, Tq, Tk, order + (size_t)blockIdx.x * Tq, hist, threadIdx.x,
-                        256);
 }
 
 // V -> V^T pre-pass.  The PV product contracts over the K/V index, so the matrix cores want, per lane, 8 V values
@@ -444,14 +431,14 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
   bool ok = true, grew = false;
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
-  auto mfma_part = [&](auto kc) __attribute__((always_inline)) {
+  auto mfma_part = [&](auto kc, auto qbc) __attribute__((always_inline)) {
     constexpr int k = decltype(kc)::value;  // the step index is a compile-time constant: every register index is static
+    constexpr int qb = decltype(qbc)::value;
     // ---- matrix cores ----
     const bf16x8 a = frag[k % kPrefetch];
     if (k >= 16) {
       const int blk = qk_blk(k), kk = qk_kk(k);
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
+      {
         if (kk == 0) {
           const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
           nxt[qb][blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.qf[qb][kk], zero, 0, 0, 0);
@@ -461,12 +448,9 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
       }
     } else {
       const int cc = k >> 2, db = k & 3;
-      if (!IMM || pv_on) {
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          st.oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_operand(&pwc[qb][4 * cc]), st.oacc[qb][db],
-                                                                    0, 0, 0);
-      }
+      if (!IMM || pv_on)
+        st.oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_operand(&pwc[qb][4 * cc]), st.oacc[qb][db],
+                                                                  0, 0, 0);
     }
   };
   auto mem_part = [&](auto kc) __attribute__((always_inline)) {
@@ -484,11 +468,11 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
     }
 
   };
-  auto vector_part = [&](auto kc) __attribute__((always_inline)) {
+  auto vector_part = [&](auto kc, auto qbc) __attribute__((always_inline)) {
     constexpr int k = decltype(kc)::value;
+    constexpr int qb = decltype(qbc)::value;
     // ---- vector ALU: slice k of the online softmax of stage s (raw dot products; 1/sqrt(d) folded into c) ----
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
+    {
       if (k < 4) {  // m_local: partial row maxima over 8 of this lane's 32 scores
         const int blk = k >> 1, r0 = 8 * (k & 1);
         int jt = j_tail;
@@ -555,18 +539,21 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
         }
       }
     }
-    if (H && k == 31) *flag_slot = __all(ok) ? 1 : 0;  // lane 0: the wave's slot; other lanes: a dummy word each
+    if (H && k == 31 && qb == QB - 1)
+      *flag_slot = __all(ok) ? 1 : 0;  // lane 0: the wave's slot; other lanes: a dummy word each
   };
   static_for(std::make_integer_sequence<int, 32>{}, [&](auto kc) __attribute__((always_inline)) {
     // matrix instruction and the memory instructions of the step first, then (fenced) the vector slice: measured
     // 1-1.5 % faster than leaving the order inside a step to the compiler (the memory instructions behind the vector
     // slice was the slowest order tried).  Issuing the MFMAs of 2, 4 or 8 steps back to back before their slices
     // (a coarser ping-pong between the two waves of a SIMD) was measured 0 / 2.5 / 6 % slower.
-    mfma_part(kc);
-    mem_part(kc);
-    __builtin_amdgcn_sched_barrier(0);
-    vector_part(kc);
-    __builtin_amdgcn_sched_barrier(0);
+    static_for(std::make_integer_sequence<int, QB>{}, [&](auto qbc) __attribute__((always_inline)) {
+      mfma_part(kc, qbc);
+      if (decltype(qbc)::value == 0) mem_part(kc);
+      __builtin_amdgcn_sched_barrier(0);
+      vector_part(kc, qbc);
+      __builtin_amdgcn_sched_barrier(0);
+    });
   });
   // O^T of the earlier stages is rescaled after this stage's PV MFMAs (rare once the running max has settled).
   // IMM: O^T now holds the products up to stage s-2 and moves to the reference maximum of stage s-1, whose product
@@ -632,6 +619,10 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
   const_u32_ptr runs = (const_u32_ptr)(p.runs + (size_t)row * p.run_stride);
   const int nruns = (int)p.nruns[row];
   int* flags = reinterpret_cast<int*>(smem + kFlagsOff);
+  // mask bits set by this workgroup during the call (thread 0 writes them, wave 0 reads them in the epilogue)
+  uint64_t* fired_bits = reinterpret_cast<uint64_t*>(smem + kFiredOff);
+  if (p.build_next)
+    for (int w = tid; w < p.W; w += kThreads) fired_bits[w] = 0;
   if (tid == 0) {  // statistics of the step: tiles skipped on entry, Skip-List entries read
     atomicAdd(p.stat_skipped_in, (unsigned long long)(p.Tk - cnt));
     atomicAdd(p.stat_runs, (unsigned long long)nruns);
@@ -747,6 +738,7 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
       const bool fired = all && !q_pinned && !k_pinned;
       if (tid == 0 && fired) {
         atomicOr(reinterpret_cast<unsigned long long*>(p.bits + (size_t)row * p.W + (j >> 6)), 1ull << (j & 63));
+        fired_bits[j >> 6] |= 1ull << (j & 63);
         ++newly;
       }
       return fired;
@@ -761,6 +753,7 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
                               p.protect_start < min(N, (j + 1) * kTile);
         if (all && !q_pinned && !k_pinned) {
           atomicOr(reinterpret_cast<unsigned long long*>(p.bits + (size_t)row * p.W + (j >> 6)), 1ull << (j & 63));
+          fired_bits[j >> 6] |= 1ull << (j & 63);
           ++newly;
         }
       }
@@ -839,35 +832,20 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
   }
 
   // ---- second epilogue: the Skip-List this row will walk in the NEXT call, compacted from the mask row as this call
-  // leaves it (the row's list is private to this workgroup: it is overwritten in place, after its last read).  The
-  // workgroup that finishes a head's last row also ranks the head's rows for the next call. ----
-  // (The kernel arguments used here are read again from the argument segment instead of being kept in scalar
-  // registers across the main loop, which has none to spare.)
+  // leaves it: the row as it was on entry (nobody else writes it) OR the bits this workgroup set, which it kept in
+  // LDS, so that nothing depends on when its own atomics become visible to its loads.  The row's list is private to
+  // this workgroup: it is overwritten in place, after its last read.  (The kernel arguments used here are read
+  // again from the argument segment instead of being kept in scalar registers across the main loop.) ----
   typedef const __attribute__((address_space(4))) FwdParams* const_params_ptr;
   const_params_ptr e = (const_params_ptr)__builtin_amdgcn_kernarg_segment_ptr();
   asm volatile("" : "+s"(e));
-  if (e->build_next) {
-    __threadfence();  // this workgroup's own mask updates (atomics of thread 0) are performed before they are read back
-    const int Tq = e->Tq, Tk = e->Tk;
-    uint32_t* const live_cnt = e->live_cnt;
-    uint32_t* const done = e->done;
-    if (wave == 0) {
-      uint32_t ns, n;
-      compact_row<true>(e->bits + (size_t)row * e->W, i, Tk, e->W, e->diagonal_first,
-                        e->runs + (size_t)row * e->run_stride, ns, n);
-      if (lane == 0) {
-        e->nruns[row] = ns;
-        live_cnt[row] = n;
-        __threadfence();  // the count is visible before this row is reported done
-        flags[0] = atomicAdd(done + bh, 1u) == (uint32_t)Tq - 1u ? 1 : 0;
-      }
-    }
-    __syncthreads();  // also: every thread is done with the staging of O, which the histogram below overwrites
-    if (flags[0]) {
-      __threadfence();
-      rank_head_rows<true>(live_cnt + (size_t)bh * Tq, Tq, Tk, e->order + (size_t)bh * Tq,
-                           reinterpret_cast<uint32_t*>(smem), tid, kThreads);
-      if (tid == 0) done[bh] = 0;  // ready for the next launch
+  if (e->build_next && wave == 0) {
+    uint32_t ns, n;
+    compact_row(e->bits + (size_t)row * e->W, [&](int w) { return fired_bits[w]; }, i, e->Tk, e->W, e->diagonal_first,
+                e->runs + (size_t)row * e->run_stride, ns, n);
+    if (lane == 0) {
+      e->nruns[row] = ns;
+      e->live_cnt[row] = n;
     }
   }
 }

@@ -51,15 +51,13 @@ hipError_t launch_fwd(const FwdParams& p, bool, hipStream_t) {
   *p.stat_skipped_in += 0;
   *p.stat_newly += 0;
   *p.stat_runs += (unsigned long long)rows;
-  if (p.build_next) {  // the epilogue rewrites the lists in full and leaves the per-head counters at zero
+  if (p.build_next) {  // the epilogue rewrites the lists in full
     memset(p.runs, 0, sizeof(uint32_t) * rows * p.run_stride);
     for (size_t r = 0; r < rows; ++r) {
       p.runs[r * p.run_stride] = (uint32_t)p.Tk << 16;
       p.nruns[r] = 1;
       p.live_cnt[r] = (uint32_t)p.Tk;
-      p.order[r] = (uint32_t)(r % p.Tq);
     }
-    for (size_t h = 0; h < rows / p.Tq; ++h) p.done[h] = 0;
   }
   return hipSuccess;
 }
