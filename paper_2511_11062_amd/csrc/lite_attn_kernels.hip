@@ -285,16 +285,23 @@ __device__ __forceinline__ u32x4 rebase(const u32x4 r, uint32_t off) {
   off = __builtin_amdgcn_readfirstlane(off);
   const uint32_t lo = __builtin_amdgcn_readfirstlane(r[0]), hi = __builtin_amdgcn_readfirstlane(r[1]);
   const uint32_t size = __builtin_amdgcn_readfirstlane(r[2]);
-  const uint64_t a = (((uint64_t)hi << 32) | lo) + off;
-  uint32_t left;  // max(size - off, 0) on the scalar unit (the compiler's saturating subtract is a vector instruction)
-  asm("s_sub_u32 %0, %1, %2\n\ts_cselect_b32 %0, 0, %0" : "=s"(left) : "s"(size), "s"(off) : "scc");
-  u32x4 o = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, left, (uint32_t)__builtin_amdgcn_readfirstlane(r[3])};
+  // base += off (the high word holds only address bits here: stride and swizzle fields are zero); size =
+  // max(size - off, 0).  Four scalar instructions; the compiler's own 64-bit add and saturating subtract take ten.
+  uint32_t nlo, nhi, left;
+  asm("s_add_u32 %0, %3, %5\n\ts_addc_u32 %1, %4, 0\n\ts_sub_u32 %2, %6, %5\n\ts_cselect_b32 %2, 0, %2"
+      : "=&s"(nlo), "=&s"(nhi), "=&s"(left)
+      : "s"(lo), "s"(hi), "s"(off), "s"(size)
+      : "scc");
+  u32x4 o = {nlo, nhi, left, (uint32_t)__builtin_amdgcn_readfirstlane(r[3])};
   return o;
 }
 
 // One 1 KB piece global -> LDS without registers: lane l's 16 bytes land at lds_addr + 16*l.  Written as inline
 // assembly so that the compiler does not order later LDS reads of OTHER buffers behind this load (it would wait
 // for vmcnt(0) before every LDS read); completion is enforced by the s_waitcnt vmcnt(0) + barrier ending a stage.
+// (Issuing a stage's four pieces of K or V back to back with one M0 update -- their LDS offsets riding in the
+// instruction offset -- was measured 3-6 % slower on the dense step: a burst of memory instructions holds up the
+// MFMA behind it.)
 // LDS address = lds_base (a wave-uniform register) + kLdsOff (a compile-time constant added on the scalar unit, so
 // that the sixteen destinations of a stage pair do not each occupy a scalar register across the main loop).
 template <int kLdsOff>
@@ -404,9 +411,17 @@ constexpr int kDmaGap = 2;    // steps between two DMA issues of a stage
 // IMM: the PV product of this stage is that of stage s-2 (same parity: its P~ and V^T buffers are those of parity
 // H), issued only if pv_on (wave-uniform: the tile it belongs to did not fire); the V^T stage loaded here is that of
 // stage s-1 (tile j_v, the other half), into the buffer of the other parity.
-template <int QB, int H, bool IMM>
+struct NoOp {
+  __device__ __forceinline__ void operator()() const {}
+};
+
+// verdict_load / verdict_commit (first stage of a tile, deferred marking only): the combine of the PREVIOUS tile's four
+// per-wave predicate results, spread over this stage -- its LDS read is issued at step 0 and used at step 12, so that
+// the wave that does it never waits for it.
+template <int QB, int H, bool IMM, class VLoad = NoOp, class VCommit = NoOp>
 __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, char* smem, int j_cur, int j_nxt,
-                                      int* flag_slot, int j_tail, int j_v = 0, bool pv_on = true) {
+                                      int* flag_slot, int j_tail, int j_v = 0, bool pv_on = true,
+                                      VLoad verdict_load = VLoad(), VCommit verdict_commit = VCommit()) {
   f32x16(&cur)[QB][2] = H ? st.sB : st.sA;
   f32x16(&nxt)[QB][2] = H ? st.sA : st.sB;
   uint32_t(&pwc)[QB][16] = (IMM && !H) ? st.pw0 : st.pw;
@@ -429,6 +444,23 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
 
   float pm[QB][4], mx[QB], m_new[QB], mc[QB], alpha[QB], lsum[QB], ta0[QB], ta1[QB], tb0[QB];
   bool ok = true, grew = false;
+  // The ragged last tile of the sequence: its columns past the end leave the row maxima and sums (one scalar compare
+  // and branch per stage, taken for one tile per row at most).  This lane's element r of block blk is column
+  // 32*blk + 8*(r>>2) + (r&3) + 4*hi of the stage: the lane-independent part is compared with one per-lane limit.
+  if (j_cur == j_tail) {
+    int lim = ln.N - (j_cur * kTile + H * kSub) - 4 * ln.hi;
+    asm volatile("" : "+v"(lim));  // keeps the compares inside this branch (else their lane masks are formed ahead of
+                                   // time, for every stage, and held in scalar registers)
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          if (32 * blk + 8 * (r >> 2) + (r & 3) >= lim) cur[qb][blk][r] = -INFINITY;
+          asm volatile("" : "+v"(cur[qb][blk][r]));  // one lane mask alive at a time
+        }
+  }
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
   auto mfma_part = [&](auto kc, auto qbc) __attribute__((always_inline)) {
@@ -466,7 +498,7 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
       else
         dma_piece<QB, kKOff + H * kStageBytes>(x - kC, krs, ln.kdma, 0u, ln.lds_wave);
     }
-
+    if (k == 0) verdict_load();
   };
   auto vector_part = [&](auto kc, auto qbc) __attribute__((always_inline)) {
     constexpr int k = decltype(kc)::value;
@@ -475,18 +507,6 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
     {
       if (k < 4) {  // m_local: partial row maxima over 8 of this lane's 32 scores
         const int blk = k >> 1, r0 = 8 * (k & 1);
-        int jt = j_tail;
-        asm volatile("" : "+s"(jt));  // a fresh scalar compare per step (a shared one becomes a lane mask + vector ops)
-        if (j_cur == jt) {  // scalar compare and branch, taken for one tile per row at most
-          // this lane's element r of block blk is column 32*blk + 8*(r>>2) + (r&3) + 4*hi of the stage: compare the
-          // lane-independent part with one per-lane limit (nothing here can be hoisted into 32 live registers)
-          int lim = ln.N - (j_cur * kTile + H * kSub) - 4 * ln.hi;
-          asm volatile("" : "+v"(lim));  // keeps the 8 compares below inside this branch (else all 32 lane masks of
-                                         // a stage are formed ahead of time and held in scalar registers)
-#pragma unroll
-          for (int r = r0; r < r0 + 8; ++r)
-            if (32 * blk + 8 * (r >> 2) + (r & 3) >= lim) cur[qb][blk][r] = -INFINITY;
-        }
         float v = cur[qb][blk][r0];
 #pragma unroll
         for (int r = r0 + 1; r < r0 + 8; ++r) v = fmaxf(v, cur[qb][blk][r]);
@@ -541,6 +561,7 @@ __device__ __forceinline__ void stage(State<QB, IMM>& st, const Lane<QB>& ln, ch
     }
     if (H && k == 31 && qb == QB - 1)
       *flag_slot = __all(ok) ? 1 : 0;  // lane 0: the wave's slot; other lanes: a dummy word each
+    if (k == 12 && qb == QB - 1) verdict_commit();
   };
   static_for(std::make_integer_sequence<int, 32>{}, [&](auto kc) __attribute__((always_inline)) {
     // matrix instruction and the memory instructions of the step first, then (fenced) the vector slice: measured
@@ -743,20 +764,30 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
       }
       return fired;
     };
-    auto finish_tile = [&](int t, int j) {
-      // the per-wave results of the finished tile meet here; one lane updates the mask
-      if (tid == 0) {
-        const int* f = flags + (t & 1) * 4;
-        int all = 1;
-        for (int w = 0; w < kWaves; ++w) all &= f[w];
+    // Deferred marking: the per-wave results of a finished tile meet in LDS; wave 0 combines them and updates the
+    // mask, not at the barrier that ends the tile (it would be late for the next stage by the latency of an LDS read,
+    // and the other three waves would wait for it at the next barrier) but during the first stage of the next tile.
+    const bool wave0 = __builtin_amdgcn_readfirstlane(wave) == 0;
+    int4 vflags = {0, 0, 0, 0};
+    const int* v_slot = flags;  // LDS slot of the tile whose verdict is pending
+    int v_j = -1;               // its K/V tile index (-1: none pending)
+    auto mark_if_fired = [&](int all, int j) {
+      if (tid == 0 && all) {
         const bool k_pinned = p.protect_len > 0 && j * kTile < p.protect_start + p.protect_len &&
                               p.protect_start < min(N, (j + 1) * kTile);
-        if (all && !q_pinned && !k_pinned) {
+        if (!q_pinned && !k_pinned) {
           atomicOr(reinterpret_cast<unsigned long long*>(p.bits + (size_t)row * p.W + (j >> 6)), 1ull << (j & 63));
           fired_bits[j >> 6] |= 1ull << (j & 63);
           ++newly;
         }
       }
+    };
+    auto verdict_load = [&]() {
+      static_assert(IMM || kWaves == 4, "four per-wave flags per tile");
+      if (wave0) vflags = *reinterpret_cast<const int4*>(v_slot);
+    };
+    auto verdict_commit = [&]() {
+      if (wave0 && v_j >= 0) mark_if_fired(vflags.x & vflags.y & vflags.z & vflags.w, v_j);
     };
     bool pv_on = false;  // IMM: the previous tile did not fire, its PV products are due
     int j_prev = j_cur;
@@ -774,9 +805,10 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
         }
         j_prev = j_cur;
       } else {
-        stage<QB, 0, false>(st, ln, smem, j_cur, j_nxt, fs, j_tail);
+        stage<QB, 0, false>(st, ln, smem, j_cur, j_nxt, fs, j_tail, 0, true, verdict_load, verdict_commit);
         stage<QB, 1, false>(st, ln, smem, j_cur, j_nxt, fs, j_tail);
-        finish_tile(t, j_cur);
+        v_slot = flags + (t & 1) * 4;
+        v_j = j_cur;
       }
       j_cur = j_nxt;
       j_nxt = j_nn;
@@ -798,8 +830,10 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
       }
       if (pv_on) mma_pv<QB>(st.oacc, st.pw, kVOff + kStageBytes, ln.vread);
     } else {
-      // drain: O^T += V^T P~^T of the last stage (odd parity buffer)
+      // drain: O^T += V^T P~^T of the last stage (odd parity buffer), and the verdict on the last tile
       mma_pv<QB>(st.oacc, st.pw, kVOff + kStageBytes, ln.vread);
+      verdict_load();
+      verdict_commit();
     }
     __syncthreads();
   }
