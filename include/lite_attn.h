@@ -147,7 +147,9 @@ int lite_attn_fwd(const void* q, const void* k, const void* v, void* out, lite_a
      hip_stream      hipStream_t on which the call's kernels are enqueued (asynchronous)
    A shape whose scratch (about the size of V plus 2*Tk+12 bytes per Q-tile row) exceeds the array is refused with
    LITE_ATTN_ESCRATCH before anything is launched: B*H*ceil(N/128) up to about 4000, e.g. the 12-head N=32760
-   layer; the larger benchmark shapes need a handle.  The first call on a GPU looks up the array's address there.
+   layer; the larger benchmark shapes need a handle.  The first call on a GPU looks up the array's address there and
+   sets the attention kernel's function attributes (no allocation, but not work to record into a graph: make the first
+   call on a GPU outside stream capture).
    Every call on a GPU uses that GPU's one array, which keeps the previous call's contents (what has to start at
    zero is cleared by the call itself): calls that overlap in time on one GPU -- two streams, two threads -- race;
    calls on one stream are safe. */
