@@ -127,8 +127,12 @@ def run_workload(la, torch, inputs, wl, thr, K, W, dev, after=None):
     return {"wall": wall, "per_step": per_step, "live_flop": live_flop, "fwd_ms": fwd_ms_total, "after": extra}
 
 
-# workloads run after the main one inside the same process (steps, warm-up), reported compactly in `other_workloads`
-OTHER_WORKLOADS = {"wan14b": [("wan1.3b_dense", 10, 1), ("longvideo", 3, 1)]}
+# workloads run after the main one inside the same process (steps, warm-up, threshold or None for the workload's
+# default), reported compactly in `other_workloads`: the dense check, the 10-step sequence at the four thresholds of
+# the sweep (about 30, 45, 60 and 70 % of the tiles skipped at the end), the first steps of the long-video layer
+OTHER_WORKLOADS = {"wan14b": [("wan1.3b_dense", 10, 1, None)] +
+                             [("wan1.3b_sweep", 10, 1, t) for t in (-2.75, -1.5, -0.5, -0.1)] +
+                             [("longvideo", 3, 1, None)]}
 
 
 def main():
@@ -215,13 +219,14 @@ def main():
 
     others = []
     if not args.no_others:
-        for name, k2, w2 in OTHER_WORKLOADS.get(wl.name, []):
+        for name, k2, w2, thr2 in OTHER_WORKLOADS.get(wl.name, []):
             wl2 = inputs.WORKLOADS[name]
+            thr2 = DEFAULT_THRESHOLD[name] if thr2 is None else thr2
             torch.cuda.empty_cache()
-            r2 = run_workload(la, torch, inputs, wl2, DEFAULT_THRESHOLD[name], k2, w2, dev)
+            r2 = run_workload(la, torch, inputs, wl2, thr2, k2, w2, dev)
             ps = r2["per_step"]
             others.append({"workload": "%s: B=%d H=%d N=%d" % (name, wl2.batch, wl2.heads, wl2.seqlen),
-                           "threshold": DEFAULT_THRESHOLD[name] if DEFAULT_THRESHOLD[name] > -1e30 else "-inf (disabled)",
+                           "threshold": thr2 if thr2 > -1e30 else "-inf (disabled)",
                            "steps": k2, "warmup": w2,
                            "ms_per_step": round(r2["wall"] / k2 * 1e3, 3),
                            "value_tflops": round(k2 * wl2.dense_flops() / r2["wall"] / 1e12, 1),
