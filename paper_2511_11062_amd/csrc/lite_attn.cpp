@@ -60,14 +60,20 @@ hipError_t launch_call(const lite_attn_desc_t& d, const Geometry& g, const ListL
   uint32_t* nruns = reinterpret_cast<uint32_t*>(lists + ll.nruns);
   uint32_t* live_cnt = reinterpret_cast<uint32_t*>(lists + ll.live_cnt);
   uint32_t* order = reinterpret_cast<uint32_t*>(lists + ll.order);
+  uint32_t* chunk_work = reinterpret_cast<uint32_t*>(lists + ll.chunk_work);
+  uint32_t* slots = reinterpret_cast<uint32_t*>(lists + ll.slots);
+  uint32_t* xcd_rows = reinterpret_cast<uint32_t*>(lists + ll.xcd_rows);
   const int diagonal_first = (d.flags & LITE_ATTN_ORDER_DIAGONAL_FIRST) ? 1 : 0;
   hipError_t e = hipSuccess;
   if (!lists_ready) {
     e = launch_compact(bits, (int)g.rows, g.Tq, g.Tk, g.W, diagonal_first, g.run_stride, runs, nruns, live_cnt, stream);
     if (e != hipSuccess) return e;
   }
-  // ranking a head's rows needs the counts of all of them: a kernel of its own (one workgroup per head)
-  e = launch_order_rows(live_cnt, g.BH, g.Tq, g.Tk, order, stream);
+  // ranking a head's rows needs the counts of all of them, dealing the ranked chunks to the XCDs those of all heads:
+  // two small kernels of their own
+  e = launch_order_rows(live_cnt, g.BH, g.Tq, g.Tk, order, chunk_work, stream);
+  if (e != hipSuccess) return e;
+  e = launch_deal_rows(chunk_work, order, g.BH, g.Tq, g.chunks, g.per_xcd, slots, xcd_rows, stream);
   if (e != hipSuccess) return e;
   e = launch_transpose_v(static_cast<const uint16_t*>(v), vt, d.stride_b, d.stride_h, d.stride_n, g.BH, d.heads,
                          d.seqlen, g.Tk, stream);
@@ -86,7 +92,7 @@ hipError_t launch_call(const lite_attn_desc_t& d, const Geometry& g, const ListL
   p.scale = 1.0f / std::sqrt((float)d.head_dim);
   p.protect_start = d.protect_start; p.protect_len = d.protect_len;
   p.rows_total = (int)g.rows;
-  p.order = order;
+  p.slots = slots; p.per_xcd = g.per_xcd; p.xcd_rows = xcd_rows;
   p.build_next = build_next ? 1 : 0;
   p.diagonal_first = diagonal_first;
   if (mid) {

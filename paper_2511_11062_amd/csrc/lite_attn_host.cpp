@@ -45,6 +45,8 @@ Geometry geometry(const lite_attn_desc_t& d) {
   g.run_stride = g.Tk / 2 + 1;
   g.BH = d.batch * d.heads;
   g.rows = (int64_t)g.BH * g.Tq;
+  g.chunks = g.BH * ((g.Tq + kChunkRows - 1) / kChunkRows);
+  g.per_xcd = ((g.chunks + 7) / 8 + 1) * kChunkRows;
   return g;
 }
 
@@ -63,6 +65,12 @@ ListLayout list_layout(const Geometry& g) {
   at += up256(sizeof(uint32_t) * (size_t)g.rows);
   l.order = at;
   at += up256(sizeof(uint32_t) * (size_t)g.rows);
+  l.chunk_work = at;
+  at += up256(sizeof(uint32_t) * (size_t)g.chunks);
+  l.slots = at;
+  at += up256(sizeof(uint32_t) * 8 * (size_t)g.per_xcd);
+  l.xcd_rows = at;
+  at += up256(sizeof(uint32_t) * 8);
   l.runs = at;
   at += up256(sizeof(uint32_t) * (size_t)g.rows * g.run_stride);
   l.total = at;

@@ -8,6 +8,9 @@
 
 namespace la {
 
+// Rows of one head that an XCD runs side by side (2 workgroups x 32 CUs): the unit of the row schedule ("chunk").
+constexpr int kChunkRows = 64;
+
 struct FwdParams {
   const uint16_t* q;
   const uint16_t* k;
@@ -27,7 +30,9 @@ struct FwdParams {
   float scale;                           // 1/sqrt(d)
   int protect_start, protect_len;
   int rows_total;                        // B*H*Tq
-  uint32_t* order;                       // [B*H][Tq]: Q tiles of each head ranked by Skip-List length, longest first
+  const uint32_t* slots;                 // [8][per_xcd]: the row (index into [B*H][Tq]) that workgroup `slot` of an
+  int per_xcd;                           //   XCD computes, written by launch_deal_rows; entries >= xcd_rows[xcd] unused
+  const uint32_t* xcd_rows;              // [8] rows dealt to each XCD
   // build_next != 0: the epilogue rewrites runs / nruns / live_cnt for the NEXT call from the mask this call leaves;
   // diagonal_first: visiting order of the lists
   int build_next, diagonal_first;
@@ -40,6 +45,8 @@ struct Geometry {
                    // ceil(Tk/2); diagonal first can split one more run at the wrap-around)
   int BH;          // batch * heads
   int64_t rows;    // BH * Tq
+  int chunks;      // BH * ceil(Tq / kChunkRows): units of the row schedule
+  int per_xcd;     // row slots per XCD in the schedule table: (ceil(chunks / 8) + 1) chunks
 };
 
 // Byte offsets of the Skip-List buffers inside one allocation (256-byte aligned pieces).  Handles keep them between
@@ -49,6 +56,9 @@ struct ListLayout {
   size_t nruns;     // [rows] uint32 runs per row
   size_t live_cnt;  // [rows] uint32 live tiles per row
   size_t order;     // [BH][Tq] uint32 row ranking
+  size_t chunk_work;  // [chunks] uint32 work of each chunk (live tiles + a per-row constant)
+  size_t slots;     // [8][per_xcd] uint32 schedule table
+  size_t xcd_rows;  // [8] uint32
   size_t runs;      // [rows][run_stride] uint32 Skip-List
   size_t total;
 };
@@ -78,7 +88,10 @@ hipError_t launch_compact(const uint64_t* bits, int rows, int Tq, int Tk, int W,
                           uint32_t* runs, uint32_t* nruns, uint32_t* live_cnt, hipStream_t st);
 hipError_t launch_transpose_v(const uint16_t* v, uint16_t* vt, int64_t stride_b, int64_t stride_h, int64_t stride_n,
                               int BH, int H, int N, int Tk, hipStream_t st);
-hipError_t launch_order_rows(const uint32_t* live_cnt, int BH, int Tq, int Tk, uint32_t* order, hipStream_t st);
+hipError_t launch_order_rows(const uint32_t* live_cnt, int BH, int Tq, int Tk, uint32_t* order, uint32_t* chunk_work,
+                             hipStream_t st);
+hipError_t launch_deal_rows(const uint32_t* chunk_work, const uint32_t* order, int BH, int Tq, int chunks, int per_xcd,
+                            uint32_t* slots, uint32_t* xcd_rows, hipStream_t st);
 hipError_t launch_fwd(const FwdParams& p, bool immediate, hipStream_t st);
 
 }  // namespace la

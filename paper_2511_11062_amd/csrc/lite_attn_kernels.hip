@@ -29,6 +29,7 @@
 //     O += V(s-2) P(s-2) runs two stages behind instead of one, so that the verdict on a tile is known before the
 //     first of its two PV products is issued; a fired tile's PV MFMAs and row sums are then dropped.
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <stdint.h>
 
 #include <utility>
@@ -166,16 +167,21 @@ __device__ __forceinline__ float other_half_sum(float x) {
   return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
 }
 
-// Row schedule.  For every head, ranks its Q-tile rows by the length of their Skip-List, longest first (counting
-// sort: one workgroup per head, histogram in LDS).  The fused kernel walks each head's rows in this order, so that
-// the rows left over at the end of the launch are the shortest ones, and spreads rank-chunks of every head over
-// all XCDs, so that every XCD gets the same mix of long and short rows whatever the sparsity of individual heads.
-__global__ __launch_bounds__(256) void order_rows_kernel(const uint32_t* __restrict__ live_cnt, int Tq, int Tk,
-                                                          uint32_t* __restrict__ order) {
-  extern __shared__ uint32_t hist[];  // Tk + 1 bins; bin b counts rows with Tk - b live tiles
+// Row schedule, first half.  For every head, ranks its Q-tile rows by the length of their Skip-List, longest first
+// (counting sort: one workgroup per head, histogram in LDS), and cuts the ranking into chunks of kChunkRows rows
+// ("rank c" = rows ranked [c*kChunkRows, (c+1)*kChunkRows)).  The chunks of all heads are numbered rank-major,
+// u = c * BH + (h + c) % BH; chunk_work[u] = the chunk's live tiles plus kRowOverhead per row (what a row costs
+// besides its tiles, in tile times).
+constexpr int kRowOverhead = 2;
+__global__ __launch_bounds__(256) void order_rows_kernel(const uint32_t* __restrict__ live_cnt, int Tq, int Tk, int BH,
+                                                          uint32_t* __restrict__ order,
+                                                          uint32_t* __restrict__ chunk_work) {
+  extern __shared__ uint32_t hist[];  // Tk + 1 bins; bin b counts rows with Tk - b live tiles; then one sum per chunk
+  uint32_t* csum = hist + (Tk + 1);
+  const int ranks = (Tq + kChunkRows - 1) / kChunkRows;
   const int bh = blockIdx.x, tid = threadIdx.x;
   const uint32_t* cnt = live_cnt + (size_t)bh * Tq;
-  for (int b = tid; b <= Tk; b += 256) hist[b] = 0;
+  for (int b = tid; b <= Tk + ranks; b += 256) hist[b] = 0;
   __syncthreads();
   for (int i = tid; i < Tq; i += 256) atomicAdd(&hist[Tk - min((int)cnt[i], Tk)], 1u);
   __syncthreads();
@@ -189,8 +195,82 @@ __global__ __launch_bounds__(256) void order_rows_kernel(const uint32_t* __restr
   }
   __syncthreads();
   for (int i = tid; i < Tq; i += 256) {
-    const uint32_t pos = atomicAdd(&hist[Tk - min((int)cnt[i], Tk)], 1u);
+    const uint32_t live = (uint32_t)min((int)cnt[i], Tk);
+    const uint32_t pos = atomicAdd(&hist[Tk - live], 1u);
     order[(size_t)bh * Tq + pos] = (uint32_t)i;
+    atomicAdd(&csum[pos / kChunkRows], live + kRowOverhead);
+  }
+  __syncthreads();
+  for (int c = tid; c < ranks; c += 256) chunk_work[(size_t)c * BH + (bh + c) % BH] = csum[c];
+}
+
+// Row schedule, second half: deals the chunks to the eight XCDs (workgroup id % 8) and writes the table the fused
+// kernel reads its row from: slots[x * per_xcd + s] = row of the s-th workgroup of XCD x (0xffffffff: none; a chunk
+// always occupies kChunkRows slots, so the chunks of a head's last rank leave some empty); xcd_rows[x] = slots in use.
+// Chunks are taken in the order of u (longest ranks first; consecutive u of a rank belong to different heads), each
+// going to the XCD with the least work so far among those holding fewer than per_xcd / kChunkRows chunks (the
+// lowest-numbered one on a tie): every XCD ends up with the same work to within about one chunk, whatever the
+// number of heads and however the sparsity differs between heads and ranks, and an XCD walks its chunks from long rows
+// to short ones.  The workgroups sharing one L2 stream the K/V of the same head (a chunk stays together).
+// The greedy pass is serial in the chunks (about 0.1 us each): wave 0 runs it with the state of XCD y in lane y --
+// key = work << 3 | y, minimum over the eight lanes by three DPP steps -- for up to kDealMax chunks; with more chunks
+// than that (64 per XCD) dealing them round-robin is balanced to within a percent or two and needs no pass at all.
+// Every workgroup of this kernel repeats the pass (same inputs, same integers) and then fills its own share of the
+// table.
+constexpr int kDealMax = 512;
+__device__ __forceinline__ uint32_t min_over_8_lanes(uint32_t key) {
+  // lanes 8k..8k+7 all end up with the minimum of their eight keys
+  key = min(key, (uint32_t)__builtin_amdgcn_update_dpp((int)key, (int)key, 0xB1, 0xf, 0xf, false));   // quad_perm 1,0,3,2
+  key = min(key, (uint32_t)__builtin_amdgcn_update_dpp((int)key, (int)key, 0x4E, 0xf, 0xf, false));   // quad_perm 2,3,0,1
+  key = min(key, (uint32_t)__builtin_amdgcn_update_dpp((int)key, (int)key, 0x141, 0xf, 0xf, false));  // row_half_mirror
+  return key;
+}
+
+__global__ __launch_bounds__(256) void deal_rows_kernel(const uint32_t* __restrict__ chunk_work,
+                                                         const uint32_t* __restrict__ order, int BH, int Tq,
+                                                         int chunks, int per_xcd, uint32_t* __restrict__ slots,
+                                                         uint32_t* __restrict__ xcd_rows) {
+  __shared__ uint32_t work[kDealMax];  // work of chunk u
+  __shared__ uint32_t dest[kDealMax];  // xcd << 29 | first slot of chunk u
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int ranks = (Tq + kChunkRows - 1) / kChunkRows;
+  const uint32_t cap = (uint32_t)(per_xcd / kChunkRows);
+  const bool greedy = chunks <= kDealMax;
+  if (greedy) {
+    for (int u = tid; u < chunks; u += 256) work[u] = chunk_work[u];
+    __syncthreads();
+    if (tid < 64) {
+      // a chunk's work is below 2^21 (64 rows of at most 16383 + kRowOverhead tiles), an XCD's below 2^27
+      uint32_t load = 0, nch = 0, w = work[0];
+      for (int u = 0; u < chunks; ++u) {
+        const uint32_t w_next = work[min(u + 1, chunks - 1)];  // read ahead: keeps the LDS latency out of the chain
+        const uint32_t key = (lane < 8 && nch < cap) ? (load << 3 | (uint32_t)lane) : 0xffffffffu;
+        const int best = (int)(__builtin_amdgcn_readfirstlane(min_over_8_lanes(key)) & 7u);
+        if (lane == best) {
+          dest[u] = ((uint32_t)best << 29) | (nch * kChunkRows);
+          load += w;
+          nch += 1;
+        }
+        w = w_next;
+      }
+      if (blockIdx.x == 0 && lane < 8) xcd_rows[lane] = nch * kChunkRows;
+    }
+    __syncthreads();
+  } else if (blockIdx.x == 0 && tid < 8) {  // round-robin: XCD x holds chunks x, x + 8, ...
+    xcd_rows[tid] = (uint32_t)((chunks - tid + 7) / 8) * kChunkRows;
+  }
+  // the table: one entry per (head, position in its ranking padded to whole chunks)
+  const long long padded = (long long)ranks * kChunkRows, total = (long long)BH * padded;
+  const long long per_wg = (total + gridDim.x - 1) / gridDim.x;
+  const long long lo = min(total, (long long)blockIdx.x * per_wg), hi = min(total, lo + per_wg);
+  for (long long idx = lo + tid; idx < hi; idx += 256) {
+    const int bh = (int)(idx / padded), pos = (int)(idx % padded);
+    const int c = pos / kChunkRows, r = pos % kChunkRows;
+    const int u = c * BH + (bh + c) % BH;
+    const uint32_t d = greedy ? dest[u] : (((uint32_t)(u & 7) << 29) | (uint32_t)((u >> 3) * kChunkRows));
+    const uint32_t s = (d & 0x1fffffffu) + (uint32_t)r;
+    if (s < (uint32_t)per_xcd)
+      slots[(size_t)(d >> 29) * per_xcd + s] = pos < Tq ? (uint32_t)bh * Tq + order[(size_t)bh * Tq + pos] : 0xffffffffu;
   }
 }
 
@@ -395,7 +475,6 @@ __device__ __forceinline__ bf16x8 load_frag(int k, const uint32_t (&kread)[8], c
   return *reinterpret_cast<LA_LDS const bf16x8*>(vread[cc] + (uint32_t)(kV + 4096 * db));
 }
 
-constexpr int kChunkRows = 64;  // rows of one head that an XCD runs side by side (2 workgroups x 32 CUs)
 constexpr int kPrefetch = 3;  // LDS fragments in flight ahead of the MFMA that consumes them
 constexpr int kDmaGap = 2;    // steps between two DMA issues of a stage
 
@@ -603,31 +682,13 @@ __global__ __launch_bounds__(Geo<QB>::kThreads, 2 / QB) void lite_attn_fwd_kerne
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lq = lane & 31;
 
-  // Consecutive workgroup ids land on different XCDs (id % 8).  The rows of every head, ranked longest first by
-  // order_rows_kernel, are cut into chunks of kChunkRows ("rank c" = rows ranked [c*kChunkRows, (c+1)*kChunkRows)).
-  // The chunks are numbered rank-major, u = c * BH + (h + c) % BH, and dealt to the XCDs round-robin (u % 8); an XCD
-  // walks its chunks in that order.  So the workgroups sharing one L2 stream the K/V of the same head, a head's
-  // chunks rotate over the XCDs (every XCD gets the same share of every rank, whatever the sparsity of individual
-  // heads), and the launch ends with the shortest rows.
+  // Consecutive workgroup ids land on different XCDs (id % 8): workgroup `slot` of an XCD computes the row that the
+  // schedule table names for it (deal_rows_kernel: chunks of kChunkRows rows of one head side by side, so that the
+  // workgroups sharing one L2 stream the same K/V; equal work per XCD; long rows first).
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int BH = p.rows_total / p.Tq;
-  const int ranks = (p.Tq + kChunkRows - 1) / kChunkRows;
-  const int len_last = p.Tq - (ranks - 1) * kChunkRows;
-  const int full_units = (ranks - 1) * BH;                    // chunks u < full_units have kChunkRows rows
-  const int k_full = full_units > xcd ? (full_units - xcd + 7) >> 3 : 0;  // how many of them this XCD owns
-  int k, r;
-  if (slot < kChunkRows * k_full) {
-    k = slot / kChunkRows;
-    r = slot % kChunkRows;
-  } else {
-    k = k_full + (slot - kChunkRows * k_full) / len_last;
-    r = (slot - kChunkRows * k_full) % len_last;
-  }
-  const int u = xcd + 8 * k;
-  if (u >= ranks * BH) return;
-  const int c = u / BH;
-  const int bh_ = ((u % BH) - (c % BH) + BH) % BH;
-  const int row = bh_ * p.Tq + (int)p.order[(size_t)bh_ * p.Tq + c * kChunkRows + r];
+  if (slot >= (int)p.xcd_rows[xcd]) return;
+  const int row = (int)p.slots[(size_t)xcd * p.per_xcd + slot];
+  if (row < 0) return;  // an empty slot behind a chunk shorter than kChunkRows
   const int i = row % p.Tq;
   const int bh = row / p.Tq;
   const int64_t base = (int64_t)(bh / p.H) * p.stride_b + (int64_t)(bh % p.H) * p.stride_h;
@@ -911,31 +972,47 @@ hipError_t launch_transpose_v(const uint16_t* v, uint16_t* vt, int64_t stride_b,
 
 constexpr int kQB = 1;  // 32 Q rows per wave, 4 waves per workgroup, 2 workgroups per CU
 
+// LDS of order_rows_kernel: Tk + 1 bins and one sum per chunk of a head (more than 64 KB for the longest sequences)
+static size_t order_lds_bytes(int Tq, int Tk) {
+  return sizeof(uint32_t) * ((size_t)(Tk + 1) + (size_t)((Tq + kChunkRows - 1) / kChunkRows));
+}
+
 hipError_t prepare_fwd() {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lite_attn_fwd_kernel<kQB, false>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, fwd_lds_bytes());
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(lite_attn_fwd_kernel<1, true>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, fwd_lds_bytes());
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(lite_attn_fwd_kernel<1, true>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, fwd_lds_bytes());
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(order_rows_kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds_bytes(16383, 16383));
 }
 
-hipError_t launch_order_rows(const uint32_t* live_cnt, int BH, int Tq, int Tk, uint32_t* order, hipStream_t st) {
-  hipLaunchKernelGGL(order_rows_kernel, dim3(BH), dim3(256), sizeof(uint32_t) * (size_t)(Tk + 1), st, live_cnt, Tq, Tk,
-                     order);
+hipError_t launch_order_rows(const uint32_t* live_cnt, int BH, int Tq, int Tk, uint32_t* order, uint32_t* chunk_work,
+                             hipStream_t st) {
+  hipLaunchKernelGGL(order_rows_kernel, dim3(BH), dim3(256), order_lds_bytes(Tq, Tk), st, live_cnt, Tq, Tk, BH, order,
+                     chunk_work);
+  return hipGetLastError();
+}
+
+hipError_t launch_deal_rows(const uint32_t* chunk_work, const uint32_t* order, int BH, int Tq, int chunks, int per_xcd,
+                            uint32_t* slots, uint32_t* xcd_rows, hipStream_t st) {
+  // every workgroup repeats the dealing and fills its share of the table: enough of them to keep the filling short
+  const long long rows = (long long)BH * Tq;
+  const int grid = (int)std::min<long long>(32, std::max<long long>(1, rows / 1024));
+  hipLaunchKernelGGL(deal_rows_kernel, dim3(grid), dim3(256), 0, st, chunk_work, order, BH, Tq, chunks, per_xcd, slots,
+                     xcd_rows);
   return hipGetLastError();
 }
 
 hipError_t launch_fwd(const FwdParams& p, bool immediate, hipStream_t st) {
-  // upper bound of the number of rows an XCD owns: ceil(chunks / 8) chunks of kChunkRows rows
-  const int BH = p.rows_total / p.Tq;
-  const int chunks = ((p.Tq + kChunkRows - 1) / kChunkRows) * BH;
-  const int per_xcd = ((chunks + 7) / 8) * kChunkRows;
+  // one workgroup per slot of the schedule table; those past an XCD's last row return at once
   if (immediate)
-    hipLaunchKernelGGL((lite_attn_fwd_kernel<1, true>), dim3(8 * per_xcd), dim3(Geo<1>::kThreads), fwd_lds_bytes(),
+    hipLaunchKernelGGL((lite_attn_fwd_kernel<1, true>), dim3(8 * p.per_xcd), dim3(Geo<1>::kThreads), fwd_lds_bytes(),
                        st, p);
   else
-    hipLaunchKernelGGL((lite_attn_fwd_kernel<kQB, false>), dim3(8 * per_xcd), dim3(Geo<kQB>::kThreads), fwd_lds_bytes(),
-                       st, p);
+    hipLaunchKernelGGL((lite_attn_fwd_kernel<kQB, false>), dim3(8 * p.per_xcd), dim3(Geo<kQB>::kThreads),
+                       fwd_lds_bytes(), st, p);
   return hipGetLastError();
 }
 

@@ -29,8 +29,20 @@ hipError_t launch_compact(const uint64_t* bits, int rows, int, int Tk, int W, in
   return hipSuccess;
 }
 
-hipError_t launch_order_rows(const uint32_t* live_cnt, int BH, int Tq, int, uint32_t* order, hipStream_t) {
+hipError_t launch_order_rows(const uint32_t* live_cnt, int BH, int Tq, int, uint32_t* order, uint32_t* chunk_work,
+                             hipStream_t) {
   for (int x = 0; x < BH * Tq; ++x) order[x] = live_cnt[x] ? (uint32_t)(x % Tq) : 0u;
+  const int chunks = BH * ((Tq + kChunkRows - 1) / kChunkRows);
+  for (int u = 0; u < chunks; ++u) chunk_work[u] = 1;
+  return hipSuccess;
+}
+
+hipError_t launch_deal_rows(const uint32_t* chunk_work, const uint32_t* order, int BH, int Tq, int chunks, int per_xcd,
+                            uint32_t* slots, uint32_t* xcd_rows, hipStream_t) {
+  volatile uint32_t sink = chunk_work[chunks - 1] + order[(size_t)BH * Tq - 1];
+  (void)sink;
+  memset(slots, 0, sizeof(uint32_t) * 8 * (size_t)per_xcd);   // the whole table may be written
+  for (int x = 0; x < 8; ++x) xcd_rows[x] = 0;
   return hipSuccess;
 }
 
@@ -44,7 +56,7 @@ hipError_t launch_fwd(const FwdParams& p, bool, hipStream_t) {
   // touches the first and last element of everything the kernel reads or writes besides q, k, v, out
   const size_t rows = (size_t)p.rows_total;
   volatile uint32_t sink = p.runs[0] + p.runs[rows * p.run_stride - 1] + p.nruns[rows - 1] + p.live_cnt[rows - 1] +
-                           p.order[rows - 1] + p.vt[(size_t)(rows / p.Tq) * 128 * ((size_t)p.Tk * 128) - 1];
+                           p.slots[8 * (size_t)p.per_xcd - 1] + p.xcd_rows[7] + p.vt[(size_t)(rows / p.Tq) * 128 * ((size_t)p.Tk * 128) - 1];
   (void)sink;
   p.bits[0] |= 0;
   p.bits[rows * p.W - 1] |= 0;

@@ -535,9 +535,11 @@ def test_arbitrary_imported_masks(density, diagonal_first):
         assert mx <= parity.MAX_REL * omax and mean <= parity.MEAN_ABS, (mx, mean, omax)
 
 
-@pytest.mark.parametrize("heads,tiles", [(1, 1), (5, 2), (9, 63), (8, 64), (17, 65), (3, 127), (40, 3), (2, 129), (7, 191)])
+@pytest.mark.parametrize("heads,tiles", [(1, 1), (5, 2), (9, 63), (8, 64), (17, 65), (3, 127), (40, 3), (2, 129), (7, 191),
+                                         (65, 8), (513, 1), (261, 65)])
 def test_row_schedule_covers_every_row(heads, tiles):
-    """Property check of the row schedule (rows ranked by Skip-List length, dealt to the XCDs in chunks of 64): for head
+    """Property check of the row schedule (rows ranked by Skip-List length, cut into chunks of 64, the chunks dealt to
+    the XCDs by work -- or round-robin when there are more than 512 of them, the last two cases): for head
     counts and row counts around the chunk and XCD boundaries, with random imported masks (so that the ranking is a
     real permutation), EVERY row of every head must come out right.  The reference here is block-masked softmax
     attention computed with PyTorch fp32 matmuls on the GPU -- a definition check on all rows, which the sampled-row
