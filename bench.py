@@ -27,7 +27,7 @@ PEAK_BF16_TFLOPS = 2500.0                  # MI355X dense bf16 MFMA, published
 # (dense_read: empty Skip-Mask; sparse_read: the mask this threshold leaves from step 1 on), so any --steps / --warmup
 # gets a figure: the mean over its timed launches.  Other workloads or thresholds report null.
 MEASURED_TRAFFIC = {
-    ("wan14b", -3.0): {"dense_read_bytes": 45.4e9, "sparse_read_bytes": 94.3e9, "write_bytes": 0.78e9,
+    ("wan14b", -3.0): {"dense_read_bytes": 44.7e9, "sparse_read_bytes": 94.2e9, "write_bytes": 0.78e9,
                        "algorithmic_min_bytes": 3.09e9, "source": "profiles/lite_attn_fwd_wan14b.txt"},
 }
 
