@@ -22,7 +22,8 @@ int check_desc(const lite_attn_desc_t* d) {
   if (d->heads > 1 && d->stride_h == 0) return LITE_ATTN_EINVAL;
   if (d->head_dim != 128 || d->tile_q != 128 || d->tile_k != 128) return LITE_ATTN_EUNSUPPORTED;
   const int64_t Tk = ((int64_t)d->seqlen + 127) / 128;
-  if (Tk > 16383) return LITE_ATTN_EUNSUPPORTED;  // row-schedule histogram (Tk + 1 bins) lives in 64 KB of LDS
+  // LDS budgets: the row schedule's histogram (Tk + 1 bins) and the fused kernel's bitmap of newly set mask bits
+  if (Tk > 16383) return LITE_ATTN_EUNSUPPORTED;
   // K/V stages are addressed with 32-bit byte offsets from the head's base pointer
   if (((int64_t)d->seqlen + 128) * d->stride_n * 2 >= ((int64_t)1 << 32)) return LITE_ATTN_EUNSUPPORTED;
   const int64_t rows = (int64_t)d->batch * d->heads * Tk;
