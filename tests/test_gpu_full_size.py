@@ -21,10 +21,11 @@ def loud(capsys):
 
 def schedule_spread_rows(name, threshold, per_group=4, xcd_heads=8, xcd_rows=3):
     """Row ids chosen to cover the launch schedule of the fused kernel: the kernel ranks every head's Q-tile rows by
-    Skip-List length and deals rank-chunks of 64 rows to the 8 XCDs (chunk c of head h goes to XCD ((h + c) mod BH)
-    mod 8).  A probe call of step 0 on the HIP path gives the mask from which steps 1.. are ranked; from it this
-    picks, for the first and the last head, `per_group` rows of the first, the middle and the last rank-chunk, and
-    `xcd_rows` rows of the first rank-chunk of each of `xcd_heads` consecutive heads (one head per XCD).  Only the
+    Skip-List length and deals rank-chunks of 64 rows to the 8 XCDs, each chunk to the XCD with the least work so far
+    (so the first rank-chunks of heads 0..7 open the eight XCDs).  A probe call of step 0 on the HIP path gives the mask
+    from which steps 1.. are ranked; from it this picks, for the first and the last head, `per_group` rows of the
+    first, the middle and the last rank-chunk, and `xcd_rows` rows of the first rank-chunk of each of `xcd_heads`
+    consecutive heads (one head per XCD).  Only the
     CHOICE of rows comes from the probe: what the oracle computes for them does not."""
     from paper_2511_11062_amd import lite_attn as la
     wl = inputs.WORKLOADS[name]
